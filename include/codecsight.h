@@ -1,0 +1,201 @@
+/*
+ * codecsight.h -- C ABI of the codec-guided sliding-window prefill hot path
+ * (CodecSight, arXiv 2604.06036) for AMD MI355X (gfx950 / CDNA4).
+ *
+ * One slide step of one batch of video streams runs, in this order:
+ *
+ *   cs_score_compact        once     codec metadata -> keep mask -> ordered kept-token list
+ *   cs_kv_rerotate          once     reused cached keys: RoPE correction by the position shift,
+ *                                    all decoder layers in one launch (values copied when repacking)
+ *   for each decoder layer:
+ *     cs_kv_refresh_scatter          freshly computed K/V rows of refresh + new tokens -> cache
+ *     cs_window_prefill_attn         causal GQA attention of those tokens over the mixed cache
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Every pointer argument is a DEVICE pointer owned by the caller, except `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).  The library allocates
+ *    nothing, keeps no per-call state, never synchronises, and enqueues all work on `stream`.
+ *  - Scalars are host values.  Strides are in ELEMENTS of the cache dtype.
+ *  - Return value: CS_OK, or a negative CS_E* code.  Argument errors are detected on the host
+ *    before anything is launched, so a failed call has no side effects on device memory.
+ *  - A cache "slot" is a row index into the KV pool: slot = block_id * 16 + offset_in_block.
+ *    The pool of one layer is addressed as  base + slot*stride_slot + kv_head*stride_head + c.
+ *  - dtype: CS_F32 (float) or CS_BF16 (bfloat16 bit patterns, uint16_t storage).
+ *  - Not checked on the device (caller's contract): slots lie inside the pool; destination
+ *    slots are unique; for a repacking re-rotation the source and destination slot sets are
+ *    disjoint; q_pos is non-decreasing inside a stream and smaller than that stream's kv_len.
+ */
+#ifndef CODECSIGHT_H_
+#define CODECSIGHT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CS_OK            0
+#define CS_EINVAL       (-1)  /* null / negative / inconsistent argument                        */
+#define CS_EUNSUPPORTED (-2)  /* dtype, head_dim, block size, group, alignment outside support  */
+#define CS_EHIP         (-3)  /* a HIP launch failed; cs_last_hip_error() holds the HIP code     */
+#define CS_EWORKSPACE   (-4)  /* workspace missing, misaligned or smaller than *_workspace()     */
+
+#define CS_F32  0
+#define CS_BF16 1
+
+#define CS_FRAME_P 0
+#define CS_FRAME_I 1
+
+#define CS_ROPE_HALF_SPLIT  0  /* pairs (i, i + d/2) */
+#define CS_ROPE_INTERLEAVED 1  /* pairs (2i, 2i + 1) */
+
+#define CS_KV_BLOCK 16         /* tokens per cache block */
+
+/* Library identification, e.g. "codecsight-mi355x 0.1 (gfx950)". Static storage. */
+const char* cs_version(void);
+
+/* HIP error code (hipError_t as int) of the most recent CS_EHIP on the calling thread, else 0. */
+int cs_last_hip_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * (a) Change scoring + ordered token compaction.       Paper Sec. 3.3.1-3.3.2, Eq. 1, 3, 4, 5,
+ *     "Temporal stabilization within a GOP", "Adapting sparsity to the model layout".
+ *
+ * The batch holds n_frames frames of n_streams streams; stream s owns frames
+ * cu_frames[s] .. cu_frames[s+1]-1 (temporal order).  Each frame has P = grid_h*grid_w patches
+ * (row-major) and T = (grid_h/group)*(grid_w/group) visual tokens (row-major token grid).
+ *
+ * Per stream, frames are visited in temporal order:
+ *   I-frame : every token is kept; the accumulated mask is reset to zero; the frame's metadata
+ *             is not read (an I-frame carries no inter-frame motion vectors).
+ *   P-frame : for patch i,  m = dx*dx + dy*dy  (integers, no rounding anywhere)
+ *               d_mv  = m >= tau_mv_sq                              (Eq. 3, squared)
+ *               d_res = use_residual && !d_mv && sad[i] >= tau_sad   (Eq. 4)
+ *               d     = d_mv | d_res | (intra && intra[i] != 0)      (Eq. 5)
+ *             acc[i] |= d (GOP accumulation; with acc_mask == NULL the patch mask is d itself),
+ *             a token is kept when any patch of its group x group block is selected.
+ * Kept tokens of all frames are then listed in frame-major, row-major order ("selected
+ * embeddings retain their original relative order").
+ *
+ * Thresholds are integers in the metadata's own units, so the mask is exact: a threshold of
+ * tau pixels on quarter-pel vectors is tau_mv_sq = (4*tau)^2; a strict '>' is '>= value+1'.
+ *
+ *  mv         in   int16  [n_frames][P][2]   (dx, dy), 4-byte aligned
+ *  sad        in   uint32 [n_frames][P]      NULL iff use_residual == 0
+ *  intra      in   uint8  [n_frames][P]      nullable: non-zero = patch overlaps an intra block
+ *  frame_type in   uint8  [n_frames]         CS_FRAME_P / CS_FRAME_I
+ *  cu_frames  in   int32  [n_streams+1]      non-decreasing, cu_frames[0]=0, last = n_frames
+ *  acc_mask   i/o  uint8  [n_streams][P]     nullable; 0/1 per patch; state carried across calls
+ *  keep_mask  out  uint8  [n_frames][T]      0/1
+ *  kept_idx   out  int32  [n_frames*T]       first kept_off[n_frames] entries valid: ids f*T+t,
+ *                                            strictly ascending; the tail is left untouched
+ *  kept_off   out  int32  [n_frames+1]       exclusive prefix of per-frame kept counts
+ *  workspace       cs_score_compact_workspace() bytes, 8-byte aligned; contents need not be
+ *                  initialised and are meaningless afterwards.  Two calls that overlap in time
+ *                  must not share a workspace.
+ * Errors: CS_EINVAL (null required pointer, n_streams < 0, n_frames < 0, grid < 1,
+ *         grid not divisible by group, sad/use_residual mismatch), CS_EUNSUPPORTED (group not in
+ *         {1,2}, n_frames*T >= 2^31), CS_EWORKSPACE, CS_EHIP.  n_streams == 0 or n_frames == 0
+ *         writes kept_off[0..n_frames] = 0 and returns CS_OK.
+ * ------------------------------------------------------------------------------------------ */
+size_t cs_score_compact_workspace(int32_t n_streams, int32_t n_frames,
+                                  int32_t grid_h, int32_t grid_w, int32_t group);
+
+int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intra,
+                     const uint8_t* frame_type, const int32_t* cu_frames, uint8_t* acc_mask,
+                     int32_t n_streams, int32_t n_frames,
+                     int32_t grid_h, int32_t grid_w, int32_t group,
+                     uint32_t tau_mv_sq, uint32_t tau_sad, int32_t use_residual,
+                     uint8_t* keep_mask, int32_t* kept_idx, int32_t* kept_off,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * (b) Position-corrected reuse of cached keys.          Paper Sec. 3.4.2, Eq. 6; Sec. 3.5
+ *     ("repacking reusable states into the destination KV cache").
+ *
+ * For every reused row r, every layer l < n_layers and every kv head h:
+ *     K[l][dst_slot[r]][h] = R(delta[r]) * K[l][src_slot[r]][h]
+ * with the one-dimensional RoPE rotation  R(D): for pair (a, b) with frequency index i,
+ *     theta_i = rope_base^(-2i/head_dim),  out_a = x_a cos(D theta_i) - x_b sin(D theta_i),
+ *                                          out_b = x_b cos(D theta_i) + x_a sin(D theta_i),
+ * (a, b) = (i, i + head_dim/2) for CS_ROPE_HALF_SPLIT, (2i, 2i+1) for CS_ROPE_INTERLEAVED.
+ * delta = p_new - p_old, signed.  Angles are formed in double precision and reduced before
+ * the single-precision sin/cos; products and the final rounding are single precision.
+ * When dst_slot != NULL (repack) V[l][dst_slot[r]][h] = V[l][src_slot[r]][h] is copied bit for
+ * bit (values carry no position).  When dst_slot == NULL the keys are rotated in place and
+ * v_cache is not touched (may be NULL).
+ *
+ *  k_cache, v_cache  i/o  pool of all layers: element (l, slot, h, c) at
+ *                         l*stride_layer + slot*stride_slot + h*stride_head + c; 16-byte aligned
+ *  src_slot, delta   in   int32 [n_rows];   dst_slot in int32 [n_rows] or NULL
+ * Errors: CS_EINVAL (null k_cache/src_slot/delta, v_cache NULL with dst_slot given, negative
+ *         sizes, rope_base <= 0), CS_EUNSUPPORTED (head_dim not a multiple of 16 or > 256,
+ *         strides not multiples of 16 bytes, unknown dtype / rope_style), CS_EHIP.
+ *         n_rows == 0 returns CS_OK without a launch.
+ * ------------------------------------------------------------------------------------------ */
+int cs_kv_rerotate(void* k_cache, void* v_cache,
+                   const int32_t* src_slot, const int32_t* dst_slot, const int32_t* delta,
+                   int64_t n_rows, int32_t n_layers, int32_t n_kv_heads, int32_t head_dim,
+                   int64_t stride_layer, int64_t stride_slot, int64_t stride_head,
+                   float rope_base, int32_t rope_style, int32_t dtype, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * (c) In-place refresh write.                            Paper Sec. 3.5 ("newly computed K/V are
+ *     written directly into the destination cache before causal attention is evaluated").
+ *
+ * One layer:  K[slot[i]][h] = k_new[i][h],  V[slot[i]][h] = v_new[i][h]  for slot[i] >= 0;
+ * a negative slot skips the token.  Pure data movement, bit exact.
+ *
+ *  k_new, v_new       in   [n_tok][n_kv_heads][head_dim] contiguous, 16-byte aligned
+ *  slot               in   int32 [n_tok]
+ *  k_cache_layer, v_cache_layer  i/o  pool already offset to the layer, 16-byte aligned
+ * Errors: CS_EINVAL (null pointer, negative size), CS_EUNSUPPORTED (row bytes or strides not a
+ *         multiple of 16 bytes, unknown dtype), CS_EHIP.  n_tok == 0 returns CS_OK.
+ * ------------------------------------------------------------------------------------------ */
+int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* slot,
+                          void* k_cache_layer, void* v_cache_layer,
+                          int64_t n_tok, int32_t n_kv_heads, int32_t head_dim,
+                          int64_t stride_slot, int64_t stride_head, int32_t dtype, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * (d) Joint prefill attention of refresh + suffix tokens over the mixed cache.   Paper Sec. 3.5
+ *     ("attention reads a combination of reused states and states computed in the current pass,
+ *     allowing suffix tokens to attend to refreshed anchors").
+ *
+ * One layer, n_streams streams in one variable-length launch.  Stream s owns query rows
+ * cu_q[s] .. cu_q[s+1]-1; query t sits at window-sequence index q_pos[t] and sees cache entries
+ * j = 0 .. q_pos[t] of its stream, entry j living in slot
+ *     block_table[s*max_blocks + j/16] * 16 + j%16.
+ * For query head h (kv head g = h / (n_q_heads / n_kv_heads)):
+ *     out[t][h] = sum_j softmax_j(softmax_scale * q[t][h] . K[slot_j][g]) * V[slot_j][g]
+ * Keys and queries arrive already rotated; no positional work happens here.
+ * CS_BF16: bf16 operands on the matrix cores, fp32 scores / statistics / accumulation, bf16
+ * result.  CS_F32: fp32 throughout.
+ *
+ *  q, out        [n_q][n_q_heads][head_dim] contiguous, 16-byte aligned
+ *  cu_q          int32 [n_streams+1], cu_q[0] = 0, cu_q[n_streams] = n_q
+ *  q_pos         int32 [n_q];  kv_len int32 [n_streams] (only an upper bound for q_pos)
+ *  block_table   int32 [n_streams][max_blocks]
+ *  workspace     cs_window_prefill_attn_workspace() bytes (may be 0, then NULL is accepted)
+ * Errors: CS_EINVAL (null pointer, negative size, n_q_heads not a multiple of n_kv_heads),
+ *         CS_EUNSUPPORTED (head_dim not in {64,128}, block_size != 16, n_q_heads/n_kv_heads > 16,
+ *         strides not multiples of 16 bytes, unknown dtype), CS_EWORKSPACE, CS_EHIP.
+ *         n_q == 0 or n_streams == 0 returns CS_OK.
+ * ------------------------------------------------------------------------------------------ */
+size_t cs_window_prefill_attn_workspace(int64_t n_q, int32_t n_streams, int32_t n_q_heads,
+                                        int32_t n_kv_heads, int32_t head_dim, int32_t dtype);
+
+int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void* v_cache_layer,
+                           const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
+                           const int32_t* block_table, int32_t max_blocks, int32_t block_size,
+                           void* out, int64_t n_q, int32_t n_streams,
+                           int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                           int64_t stride_slot, int64_t stride_head, float softmax_scale,
+                           int32_t dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODECSIGHT_H_ */

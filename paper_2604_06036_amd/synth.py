@@ -1,0 +1,226 @@
+"""Seeded synthetic inputs shaped like the paper's streaming-video workloads.
+
+This module only draws random inputs (codec metadata, frame-type schedules, block tables,
+Q/K/V tensors).  It applies none of the method's arithmetic -- no thresholds, no masks, no
+rotations, no attention -- so it can feed both the HIP path and the CPU oracle.
+
+Geometry follows the paper: 448x448 frames give a 16x16 grid of merged visual tokens, I+P GOPs,
+one window per stride, many independent streams.  The videos, questions and model weights behind
+the paper's evaluation are not available here; these streams stand in for them.
+
+Recipe (per stream s of workload w, rng = default_rng(SeedSequence([0xC0DEC, w.seed_id, s]))):
+  frame types  I-frames every `gop` frames, phase chosen so that slot `i_slot` of the NEW window
+               is an I-frame; history = 2*max(gop) warm-up frames + the old window + the stride.
+  moving blobs discs on the patch grid, radii U[1.5, 3.5] patches scaled by one bisected factor
+               so that the rasterised area is within 2 p.p. of the stream's moving fraction;
+               centres random-walk N(0, 0.5^2) patches per frame, reflected at the borders.
+  MV           int16 quarter-pel components: round(N(0,1)) outside blobs, round(N(0,24)) inside
+               (24 is the standard deviation).
+  SAD          uint32 round(Gamma(k=2, theta=50)), multiplied by 10 inside blobs.
+  I-frames     carry zero metadata.
+  Q/K/V, cache N(0,1), float32 then cast to the workload dtype.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Tuple
+
+import numpy as np
+
+FRAME_P = 0
+FRAME_I = 1
+KV_BLOCK = 16
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    seed_id: int
+    n_streams: int
+    dtype: str                      # "f32" | "bf16"
+    window: int                     # frames per window (W)
+    stride: int                     # new frames per slide (S)
+    grid_h: int
+    grid_w: int
+    n_text: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    rope_base: float
+    n_layers: int
+    gop_choices: Tuple[int, ...]
+    i_slot: int                     # I-frame slot in the new window; -1 = uniform over the GOP
+    moving: Tuple[str, float, float]  # ("const", m, _) | ("uniform", lo, hi) | ("beta", a, b)
+    group: int = 1
+    tau_mv_sq: int = 17             # |MV| > 4 quarter-pel  <=>  dx^2+dy^2 >= 17
+    tau_sad: int = 401              # SAD > 400
+    use_residual: bool = True
+    dense_history: bool = False     # overlap frames cached unpruned (literal "dense rows" reading)
+    shuffle_blocks: bool = True
+
+    @property
+    def patches(self) -> int:
+        return self.grid_h * self.grid_w
+
+    @property
+    def tokens_per_frame(self) -> int:
+        return (self.grid_h // self.group) * (self.grid_w // self.group)
+
+    @property
+    def history(self) -> int:
+        return 2 * max(self.gop_choices) + self.window + self.stride
+
+    @property
+    def position_shift(self) -> int:
+        return -self.stride * self.tokens_per_frame
+
+
+# The five configurations of the benchmark definition (3p / 3d are the two readings of the
+# long-window case: cache pruned as the method would leave it, or holding dense rows).
+CFG0 = Workload("cfg0_tiny_f32", 0, 1, "f32", 4, 1, 16, 16, 16, 2, 1, 64, 1e4, 1,
+                (4,), 0, ("const", 0.20, 0.0), shuffle_blocks=False)
+CFG1 = Workload("cfg1_qwen7b_1stream", 1, 1, "bf16", 8, 1, 16, 16, 64, 28, 4, 128, 1e6, 28,
+                (8,), 0, ("const", 0.25, 0.0), shuffle_blocks=False)
+CFG2 = Workload("cfg2_qwen7b_32streams", 2, 32, "bf16", 8, 1, 16, 16, 64, 28, 4, 128, 1e6, 28,
+                (8,), -1, ("uniform", 0.05, 0.40))
+CFG3P = Workload("cfg3p_longwindow_pruned", 3, 1, "bf16", 16, 2, 26, 46, 128, 28, 4, 128, 1e6, 28,
+                 (16,), 0, ("const", 0.15, 0.0), shuffle_blocks=False)
+CFG3D = replace(CFG3P, name="cfg3d_longwindow_dense", dense_history=True)
+CFG4 = Workload("cfg4_internlm7b_64streams", 4, 64, "bf16", 8, 1, 16, 16, 32, 32, 8, 128, 1e6, 32,
+                (4, 8, 16), -1, ("beta", 2.0, 8.0))
+
+WORKLOADS = {w.name: w for w in (CFG0, CFG1, CFG2, CFG3P, CFG3D, CFG4)}
+
+
+def small_variant(w: Workload, n_streams: int | None = None, n_layers: int | None = None) -> Workload:
+    """Same shapes with fewer streams / layers (parity cases the CPU oracle finishes quickly)."""
+    return replace(w, n_streams=n_streams or w.n_streams, n_layers=n_layers or w.n_layers)
+
+
+def _rng(w: Workload, *tag: int) -> np.random.Generator:
+    return np.random.default_rng(np.random.SeedSequence([0xC0DEC, w.seed_id, *tag]))
+
+
+def _reflect(x: np.ndarray, hi: float) -> np.ndarray:
+    x = np.abs(x)
+    return np.where(x > hi, 2.0 * hi - x, x)
+
+
+def _blob_mask(cy, cx, rad, grid_h, grid_w) -> np.ndarray:
+    """[n_frames, P] bool: patch centre inside any disc.  cy, cx: [n_frames, n_blobs]."""
+    yy, xx = np.meshgrid(np.arange(grid_h) + 0.5, np.arange(grid_w) + 0.5, indexing="ij")
+    yy = yy.reshape(1, 1, -1)
+    xx = xx.reshape(1, 1, -1)
+    d2 = (yy - cy[..., None]) ** 2 + (xx - cx[..., None]) ** 2
+    return (d2 <= (rad[None, :, None] ** 2)).any(axis=1)
+
+
+@dataclass
+class StreamMeta:
+    gop: int
+    moving_target: float
+    frame_type: np.ndarray   # uint8 [H]
+    mv: np.ndarray           # int16 [H, P, 2]
+    sad: np.ndarray          # uint32 [H, P]
+    blob: np.ndarray         # bool [H, P] (where the generator put motion; informational)
+
+
+def stream_metadata(w: Workload, s: int) -> StreamMeta:
+    """Codec metadata of the whole history of stream s (oldest frame first)."""
+    rng = _rng(w, s)
+    n_hist, n_patch = w.history, w.patches
+    gop = int(rng.choice(np.asarray(w.gop_choices)))
+    i_slot = w.i_slot if w.i_slot >= 0 else int(rng.integers(0, gop))
+    kind, a, b = w.moving
+    if kind == "const":
+        target = a
+    elif kind == "uniform":
+        target = float(rng.uniform(a, b))
+    else:
+        target = float(rng.beta(a, b))
+
+    # frame types: the new window occupies history slots [H-W, H); its slot i_slot is an I-frame
+    anchor = n_hist - w.window + i_slot
+    idx = np.arange(n_hist)
+    frame_type = np.where((idx - anchor) % gop == 0, FRAME_I, FRAME_P).astype(np.uint8)
+
+    # blobs
+    mean_area = np.pi * 2.5 ** 2
+    n_blobs = max(1, int(round(target * n_patch / mean_area)))
+    rad0 = rng.uniform(1.5, 3.5, size=n_blobs)
+    cy0 = rng.uniform(0.0, w.grid_h, size=n_blobs)
+    cx0 = rng.uniform(0.0, w.grid_w, size=n_blobs)
+    lo, hi = 0.05, 6.0
+    for _ in range(40):                      # bisect one common radius scale on the first frame
+        mid = 0.5 * (lo + hi)
+        frac = _blob_mask(cy0[None], cx0[None], rad0 * mid, w.grid_h, w.grid_w).mean()
+        if frac > target:
+            hi = mid
+        else:
+            lo = mid
+    rad = rad0 * 0.5 * (lo + hi)
+    steps = rng.normal(0.0, 0.5, size=(n_hist, n_blobs, 2))
+    steps[0] = 0.0
+    cy = _reflect(cy0[None] + np.cumsum(steps[..., 0], axis=0), float(w.grid_h))
+    cx = _reflect(cx0[None] + np.cumsum(steps[..., 1], axis=0), float(w.grid_w))
+    blob = _blob_mask(cy, cx, rad, w.grid_h, w.grid_w)
+
+    sigma = np.where(blob, 24.0, 1.0)[..., None]
+    mv = np.rint(rng.normal(0.0, 1.0, size=(n_hist, n_patch, 2)) * sigma)
+    mv = np.clip(mv, -32768, 32767).astype(np.int16)
+    sad = np.rint(rng.gamma(2.0, 50.0, size=(n_hist, n_patch)) * np.where(blob, 10.0, 1.0))
+    sad = sad.astype(np.uint32)
+    is_i = frame_type == FRAME_I
+    mv[is_i] = 0
+    sad[is_i] = 0
+    return StreamMeta(gop, target, frame_type, mv, sad, blob)
+
+
+@dataclass
+class BatchMeta:
+    """History of all streams, stream-major: frame f of stream s is row s*H + f."""
+    workload: Workload
+    frame_type: np.ndarray   # uint8 [B*H]
+    mv: np.ndarray           # int16 [B*H, P, 2]
+    sad: np.ndarray          # uint32 [B*H, P]
+    gop: np.ndarray          # int32 [B]
+    moving_target: np.ndarray
+
+    def rows(self, first: int, count: int) -> np.ndarray:
+        """Row indices of history frames [first, first+count) of every stream, stream-major."""
+        h = self.workload.history
+        return (np.arange(self.workload.n_streams)[:, None] * h + first + np.arange(count)[None]).reshape(-1)
+
+
+def batch_metadata(w: Workload) -> BatchMeta:
+    metas = [stream_metadata(w, s) for s in range(w.n_streams)]
+    return BatchMeta(
+        w,
+        np.concatenate([m.frame_type for m in metas]),
+        np.concatenate([m.mv for m in metas]),
+        np.concatenate([m.sad for m in metas]),
+        np.asarray([m.gop for m in metas], dtype=np.int32),
+        np.asarray([m.moving_target for m in metas]),
+    )
+
+
+def block_ids(w: Workload, n_blocks_needed: int, tag: int = 0) -> np.ndarray:
+    """A pool of `n_blocks_needed` distinct physical block ids: shuffled, or 0..n-1 in order."""
+    ids = np.arange(n_blocks_needed, dtype=np.int32)
+    if w.shuffle_blocks:
+        _rng(w, 0x0B10C, tag).shuffle(ids)
+    return ids
+
+
+def normal_tensor(w: Workload, tag: Tuple[int, ...], shape, device="cpu"):
+    """N(0,1) tensor in the workload dtype, drawn in float32 then cast.  Returns a torch tensor.
+
+    The seed depends on (workload, tag) only; CPU and GPU generators give different streams, so
+    a test that compares against the oracle draws on the CPU and copies.
+    """
+    import torch
+    seed = int(np.random.SeedSequence([0xC0DEC, w.seed_id, 0x7E50, *tag]).generate_state(1)[0])
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    x = torch.randn(shape, generator=gen, device=device, dtype=torch.float32)
+    return x if w.dtype == "f32" else x.to(torch.bfloat16)
