@@ -1,0 +1,177 @@
+"""Thin ctypes binding over libcodecsight.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point (include/codecsight.h) and
+takes torch tensors that already live on the GPU; the work is enqueued on torch's current stream.
+Nothing here computes anything, and there is no fallback: a missing library is an ImportError at
+first use, and a non-zero status code raises CodecSightError.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcodecsight.so")
+
+CS_OK, CS_EINVAL, CS_EUNSUPPORTED, CS_EHIP, CS_EWORKSPACE = 0, -1, -2, -3, -4
+CS_F32, CS_BF16 = 0, 1
+CS_FRAME_P, CS_FRAME_I = 0, 1
+CS_ROPE_HALF_SPLIT, CS_ROPE_INTERLEAVED = 0, 1
+CS_KV_BLOCK = 16
+
+_ERR = {CS_EINVAL: "CS_EINVAL", CS_EUNSUPPORTED: "CS_EUNSUPPORTED", CS_EHIP: "CS_EHIP",
+        CS_EWORKSPACE: "CS_EWORKSPACE"}
+
+EXPORTS = ("cs_version", "cs_last_hip_error", "cs_score_compact_workspace", "cs_score_compact",
+           "cs_kv_rerotate", "cs_kv_refresh_scatter", "cs_window_prefill_attn_workspace",
+           "cs_window_prefill_attn")
+
+
+class CodecSightError(RuntimeError):
+    def __init__(self, fn: str, code: int, hip: int = 0):
+        self.code = code
+        self.hip = hip
+        extra = f" (hipError {hip})" if code == CS_EHIP else ""
+        super().__init__(f"{fn} failed: {_ERR.get(code, code)}{extra}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Opens the HIP library (built by `python -m paper_2604_06036_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_06036_amd.build`; "
+                          "there is no CPU fallback")
+    L = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i32, i64, u32, sz, f32 = c.c_void_p, c.c_int32, c.c_int64, c.c_uint32, c.c_size_t, c.c_float
+    L.cs_version.restype = c.c_char_p
+    L.cs_version.argtypes = []
+    L.cs_last_hip_error.restype = c.c_int
+    L.cs_last_hip_error.argtypes = []
+    L.cs_score_compact_workspace.restype = sz
+    L.cs_score_compact_workspace.argtypes = [i32, i32, i32, i32, i32]
+    L.cs_score_compact.restype = c.c_int
+    L.cs_score_compact.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, u32, u32, i32,
+                                   vp, vp, vp, vp, sz, vp]
+    L.cs_kv_rerotate.restype = c.c_int
+    L.cs_kv_rerotate.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, i64, i64, f32, i32, i32, vp]
+    L.cs_kv_refresh_scatter.restype = c.c_int
+    L.cs_kv_refresh_scatter.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i64, i64, i32, vp]
+    L.cs_window_prefill_attn_workspace.restype = sz
+    L.cs_window_prefill_attn_workspace.argtypes = [i64, i32, i32, i32, i32, i32]
+    L.cs_window_prefill_attn.restype = c.c_int
+    L.cs_window_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, i64, i32, i32, i32,
+                                         i32, i64, i64, f32, i32, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _need(fn: str, t: Optional[torch.Tensor], n: int, what: str):
+    """Marshalling guard: an index / data tensor shorter than the count passed beside it would make
+    the kernel read past its end, so it is refused here."""
+    if t is not None and t.numel() < n:
+        raise ValueError(f"{fn}: {what} holds {t.numel()} elements, {n} needed")
+
+
+def _check(fn: str, code: int):
+    if code != CS_OK:
+        raise CodecSightError(fn, code, lib().cs_last_hip_error() if code == CS_EHIP else 0)
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return CS_F32
+    if t.dtype == torch.bfloat16:
+        return CS_BF16
+    raise CodecSightError("dtype", CS_EUNSUPPORTED)
+
+
+def cs_version() -> str:
+    return lib().cs_version().decode()
+
+
+def cs_score_compact_workspace(n_streams, n_frames, grid_h, grid_w, group) -> int:
+    return int(lib().cs_score_compact_workspace(n_streams, n_frames, grid_h, grid_w, group))
+
+
+def cs_score_compact(mv, sad, intra, frame_type, cu_frames, acc_mask, n_streams, n_frames, grid_h,
+                     grid_w, group, tau_mv_sq, tau_sad, use_residual, keep_mask, kept_idx, kept_off,
+                     workspace, workspace_bytes=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = "cs_score_compact"
+    n_patch, n_tok = grid_h * grid_w, (grid_h // max(1, group)) * (grid_w // max(1, group))
+    _need(fn, mv, n_frames * n_patch * 2, "mv"); _need(fn, sad, n_frames * n_patch, "sad")
+    _need(fn, intra, n_frames * n_patch, "intra"); _need(fn, frame_type, n_frames, "frame_type")
+    _need(fn, cu_frames, n_streams + 1, "cu_frames"); _need(fn, acc_mask, n_streams * n_patch, "acc_mask")
+    _need(fn, keep_mask, n_frames * n_tok, "keep_mask"); _need(fn, kept_idx, n_frames * n_tok, "kept_idx")
+    _need(fn, kept_off, n_frames + 1, "kept_off")
+    if workspace is not None and workspace.numel() * workspace.element_size() < workspace_bytes:
+        raise ValueError("cs_score_compact: workspace tensor smaller than workspace_bytes")
+    _check("cs_score_compact", lib().cs_score_compact(
+        _ptr(mv), _ptr(sad), _ptr(intra), _ptr(frame_type), _ptr(cu_frames), _ptr(acc_mask),
+        n_streams, n_frames, grid_h, grid_w, group, tau_mv_sq, tau_sad, int(bool(use_residual)),
+        _ptr(keep_mask), _ptr(kept_idx), _ptr(kept_off), _ptr(workspace), workspace_bytes, _stream()))
+
+
+def cs_kv_rerotate(k_cache, v_cache, src_slot, dst_slot, delta, n_rows, n_layers, n_kv_heads, head_dim,
+                   stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype):
+    for t, what in ((src_slot, "src_slot"), (dst_slot, "dst_slot"), (delta, "delta")):
+        _need("cs_kv_rerotate", t, n_rows, what)
+    _check("cs_kv_rerotate", lib().cs_kv_rerotate(
+        _ptr(k_cache), _ptr(v_cache), _ptr(src_slot), _ptr(dst_slot), _ptr(delta), n_rows, n_layers,
+        n_kv_heads, head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype,
+        _stream()))
+
+
+def cs_kv_refresh_scatter(k_new, v_new, slot, k_cache_layer, v_cache_layer, n_tok, n_kv_heads, head_dim,
+                          stride_slot, stride_head, dtype):
+    fn = "cs_kv_refresh_scatter"
+    _need(fn, slot, n_tok, "slot"); _need(fn, k_new, n_tok * n_kv_heads * head_dim, "k_new")
+    _need(fn, v_new, n_tok * n_kv_heads * head_dim, "v_new")
+    _check("cs_kv_refresh_scatter", lib().cs_kv_refresh_scatter(
+        _ptr(k_new), _ptr(v_new), _ptr(slot), _ptr(k_cache_layer), _ptr(v_cache_layer), n_tok,
+        n_kv_heads, head_dim, stride_slot, stride_head, dtype, _stream()))
+
+
+def cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, head_dim, dtype) -> int:
+    return int(lib().cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, head_dim,
+                                                      dtype))
+
+
+def cs_window_prefill_attn(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks,
+                           block_size, out, n_q, n_streams, n_q_heads, n_kv_heads, head_dim, stride_slot,
+                           stride_head, softmax_scale, dtype, workspace=None, workspace_bytes=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = "cs_window_prefill_attn"
+    _need(fn, q, n_q * n_q_heads * head_dim, "q"); _need(fn, out, n_q * n_q_heads * head_dim, "out")
+    _need(fn, cu_q, n_streams + 1, "cu_q"); _need(fn, q_pos, n_q, "q_pos"); _need(fn, kv_len, n_streams, "kv_len")
+    _need(fn, block_table, n_streams * max_blocks, "block_table")
+    if workspace is not None and workspace.numel() * workspace.element_size() < workspace_bytes:
+        raise ValueError("cs_window_prefill_attn: workspace tensor smaller than workspace_bytes")
+    _check("cs_window_prefill_attn", lib().cs_window_prefill_attn(
+        _ptr(q), _ptr(k_cache_layer), _ptr(v_cache_layer), _ptr(cu_q), _ptr(q_pos), _ptr(kv_len),
+        _ptr(block_table), max_blocks, block_size, _ptr(out), n_q, n_streams, n_q_heads, n_kv_heads,
+        head_dim, stride_slot, stride_head, softmax_scale, dtype, _ptr(workspace), workspace_bytes,
+        _stream()))

@@ -1,0 +1,400 @@
+// (d) Joint prefill attention of refresh + suffix tokens over the mixed window cache, gfx950.
+//
+// Paper Sec. 3.5: refresh tokens and the normal suffix run one joint prefill pass; at each layer
+// causal attention reads a cache that mixes reused (position-corrected) states with states
+// written in the current pass.  Causality follows the window-sequence index of each query.
+//
+// bf16 kernel (matrix cores).  One workgroup = 4 waves = a tile of 128 "rows", a row being one
+// (query token, query head of one kv group) pair, so the K/V tiles a workgroup stages in LDS are
+// shared by all query heads of the group.  Keys are swept in tiles of 64 through LDS:
+//   S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K fragment from LDS (ds_read_b128),
+//                    B = Q^T fragment held in registers for the whole sweep;
+//   online softmax   fp32, per-lane statistics: in the S^T layout a lane owns one query and 16
+//                    of its 32 keys, the two half-waves exchange the running max once per tile;
+//   O^T += V^T P^T   P^T is already in B-operand layout (no LDS round trip); the V^T fragment is
+//                    fetched from the row-major V tile with the LDS transpose read
+//                    (ds_read_b64_tr_b16), so V is never transposed in memory.
+// Global loads of the next K/V tile are issued before the current tile is computed.  Tiles that
+// lie wholly above a wave's causal frontier are skipped by that wave; only tiles that straddle a
+// frontier pay for masking.  Cache rows past the workgroup's frontier are never read (they may be
+// unallocated) and are staged as zeros so that 0 * garbage cannot produce NaN.
+//
+// fp32 kernel: plain SIMT, one wave per (query, head), keys strided over lanes, online softmax
+// per lane and a final cross-lane merge.  It exists for fp32 caches (small validation shapes).
+#include <math.h>
+
+#include "common.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+struct AttnParams {
+  const void* __restrict__ q;
+  const void* __restrict__ k;
+  const void* __restrict__ v;
+  void* __restrict__ out;
+  const int32_t* __restrict__ cu_q;
+  const int32_t* __restrict__ q_pos;
+  const int32_t* __restrict__ block_table;
+  int64_t stride_slot, stride_head;
+  int32_t max_blocks, n_streams, n_q_heads, n_kv_heads, group;
+  float scale, scale_log2e;
+  int64_t n_q;
+};
+
+constexpr int kBM = 128;   // rows per workgroup (4 waves x 32)
+constexpr int kBN = 64;    // keys per LDS tile
+constexpr float kNegInf = -INFINITY;
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(cs::f32_to_bf16(lo)) | (static_cast<uint32_t>(cs::f32_to_bf16(hi)) << 16);
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) {
+  constexpr int KP = D + 8;            // K tile pitch (elements): rows shift by 4 banks
+  constexpr int VP = D + 32;           // V tile pitch: rows shift by 16 banks (transpose reads)
+  constexpr int STEPS = D / 16;        // contraction steps of S^T
+  constexpr int DB = D / 32;           // 32-wide blocks of the head dimension in O^T
+  constexpr int CPR = D / 8;           // 16-byte chunks per cache row
+  constexpr int RPP = 256 / CPR;       // rows staged per pass by the whole workgroup
+  constexpr int PASSES = kBN / RPP;
+
+  __shared__ __attribute__((aligned(16))) uint16_t sK[kBN * KP];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kBN * VP];
+
+  // ---- which (stream, row tile) is this workgroup?  longest tiles of a stream come first
+  int x = blockIdx.x, s = 0, q0 = 0, rows_total = 0, n_row_tiles = 0;
+  for (; s < p.n_streams; ++s) {
+    q0 = p.cu_q[s];
+    rows_total = (p.cu_q[s + 1] - q0) * p.group;
+    n_row_tiles = (rows_total + kBM - 1) / kBM;
+    if (x < n_row_tiles) break;
+    x -= n_row_tiles;
+  }
+  if (s == p.n_streams) return;
+  const int r_tile = (n_row_tiles - 1 - x) * kBM;
+  const int kvh = blockIdx.y;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, h = lane >> 5;
+
+  // ---- this lane's row (query token, head) and causal frontier
+  const int row = r_tile + wave * 32 + n;
+  const bool valid = row < rows_total;
+  const int row_c = valid ? row : rows_total - 1;
+  const int tok = q0 + row_c / p.group;
+  const int head = kvh * p.group + row_c % p.group;
+  const int lim = valid ? p.q_pos[tok] : -1;
+
+  const int wg_last = min(r_tile + kBM, rows_total) - 1;
+  const int wg_max = p.q_pos[q0 + wg_last / p.group];
+  const int w_first = r_tile + wave * 32;
+  const bool wave_live = w_first < rows_total;
+  const int w_last = min(w_first + 31, rows_total - 1);
+  const int wave_min = wave_live ? p.q_pos[q0 + w_first / p.group] : -1;
+  const int wave_max = wave_live ? p.q_pos[q0 + w_last / p.group] : -1;
+  const int n_key_tiles = wg_max / kBN + 1;
+
+  // ---- Q^T fragments: lane = (query n, half h) holds d-slice [16*step + 8h, +8)
+  const uint16_t* qrow = static_cast<const uint16_t*>(p.q) +
+                         (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
+  bf16x8 qf[STEPS];
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st)
+    qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(qrow + 16 * st + 8 * h));
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = kNegInf, l_run = 0.f;
+
+  // ---- staging of K/V tiles: thread -> (row tid / CPR + pass * RPP, chunk tid % CPR)
+  const int st_row = tid / CPR, st_chunk = tid % CPR;
+  const int32_t* bt = p.block_table + static_cast<int64_t>(s) * p.max_blocks;
+  const uint16_t* kbase = static_cast<const uint16_t*>(p.k) + kvh * p.stride_head + st_chunk * 8;
+  const uint16_t* vbase = static_cast<const uint16_t*>(p.v) + kvh * p.stride_head + st_chunk * 8;
+  cs::u32x4 kreg[PASSES], vreg[PASSES];
+
+  auto fetch = [&](int key_tile) {
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      const int j = key_tile * kBN + st_row + i * RPP;
+      kreg[i] = cs::u32x4{0, 0, 0, 0};
+      vreg[i] = cs::u32x4{0, 0, 0, 0};
+      if (j <= wg_max) {
+        const int64_t slot = static_cast<int64_t>(bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
+        kreg[i] = *reinterpret_cast<const cs::u32x4*>(kbase + slot * p.stride_slot);
+        vreg[i] = *reinterpret_cast<const cs::u32x4*>(vbase + slot * p.stride_slot);
+      }
+    }
+  };
+
+  fetch(0);
+  for (int kt = 0; kt < n_key_tiles; ++kt) {
+    __syncthreads();                       // everyone is done reading the previous tile
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      const int r = st_row + i * RPP;
+      *reinterpret_cast<cs::u32x4*>(&sK[r * KP + st_chunk * 8]) = kreg[i];
+      *reinterpret_cast<cs::u32x4*>(&sV[r * VP + st_chunk * 8]) = vreg[i];
+    }
+    __syncthreads();
+    if (kt + 1 < n_key_tiles) fetch(kt + 1);
+
+    const int j0 = kt * kBN;
+    if (j0 > wave_max) continue;           // wholly above this wave's frontier (wave-uniform)
+
+    // ---- S^T = K Q^T for the 64 keys of the tile: two 32-key blocks
+    f32x16 sacc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+#pragma unroll
+      for (int st = 0; st < STEPS; ++st) {
+        const bf16x8 a = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const cs::u32x4*>(&sK[(kb * 32 + n) * KP + 16 * st + 8 * h]));
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], sacc[kb], 0, 0, 0);
+      }
+    }
+    // register r of block kb is key j0 + 32 kb + 8 (r / 4) + 4 h + r % 4 of query n
+    if (j0 + kBN - 1 > wave_min) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
+          if (key > lim) sacc[kb][r] = kNegInf;
+        }
+    }
+    float t_max = kNegInf;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[kb][r]);
+    t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
+    const float m_new = fmaxf(m_run, t_max);
+    const float m_use = m_new == kNegInf ? 0.f : m_new;      // rows with nothing visible yet
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * p.scale_log2e);
+    const float m_scaled = m_use * p.scale_log2e;
+    float t_sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], p.scale_log2e, -m_scaled));
+        sacc[kb][r] = e;
+        t_sum += e;
+      }
+    l_run = fmaf(l_run, alpha, t_sum);
+    m_run = m_new;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T.  MFMA (kb, mm) contracts S registers 8mm..8mm+7 of block kb; slot
+    //      8h + i of the contraction is key 32 kb + 16 mm + 8 (i / 4) + 4 h + i % 4.
+    bf16x8 pb[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        cs::u32x4 w;
+        w.x = pack_bf16x2(sacc[kb][8 * mm + 0], sacc[kb][8 * mm + 1]);
+        w.y = pack_bf16x2(sacc[kb][8 * mm + 2], sacc[kb][8 * mm + 3]);
+        w.z = pack_bf16x2(sacc[kb][8 * mm + 4], sacc[kb][8 * mm + 5]);
+        w.w = pack_bf16x2(sacc[kb][8 * mm + 6], sacc[kb][8 * mm + 7]);
+        pb[kb][mm] = __builtin_bit_cast(bf16x8, w);
+      }
+    // transpose read: lane i of a 16-lane group supplies &V[key0 + i / 4][col0 + 4 (i % 4)] and
+    // receives V[key0 + 0..3][col0 + i]
+    const int i16 = lane & 15, gid = (lane >> 4) & 1;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int col = 32 * db + 16 * gid + 4 * (i16 & 3);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+          const int key0 = 32 * kb + 16 * mm + 4 * h + (i16 >> 2);
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4*)(&sV[key0 * VP + col]));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4*)(&sV[(key0 + 8) * VP + col]));
+          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kb][mm],
+                                                         o[db], 0, 0, 0);
+        }
+    }
+  }
+
+  // ---- normalise and store: register r of block db is d = 32 db + 8 (r / 4) + 4 h + r % 4
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (valid) {
+    const float inv = 1.f / l_tot;
+    uint16_t* orow = static_cast<uint16_t*>(p.out) +
+                     (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        cs::u32x2 w;
+        w.x = pack_bf16x2(o[db][4 * rq + 0] * inv, o[db][4 * rq + 1] * inv);
+        w.y = pack_bf16x2(o[db][4 * rq + 2] * inv, o[db][4 * rq + 3] * inv);
+        *reinterpret_cast<cs::u32x2*>(orow + 32 * db + 8 * rq + 4 * h) = w;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void window_attn_f32_kernel(AttnParams p) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t unit = static_cast<int64_t>(blockIdx.x) * 4 + wave;      // (query, head)
+  if (unit >= p.n_q * p.n_q_heads) return;
+  const int tok = static_cast<int>(unit / p.n_q_heads);
+  const int head = static_cast<int>(unit - static_cast<int64_t>(tok) * p.n_q_heads);
+  const int kvh = head / p.group;
+  int s = 0;
+  while (s + 1 < p.n_streams && p.cu_q[s + 1] <= tok) ++s;
+  const int32_t* bt = p.block_table + static_cast<int64_t>(s) * p.max_blocks;
+  const int lim = p.q_pos[tok];
+
+  const float* qrow = static_cast<const float*>(p.q) + (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
+  float qv[D], acc[D];
+#pragma unroll
+  for (int c = 0; c < D; c += 4) {
+    const float4 t = *reinterpret_cast<const float4*>(qrow + c);
+    qv[c] = t.x; qv[c + 1] = t.y; qv[c + 2] = t.z; qv[c + 3] = t.w;
+  }
+#pragma unroll
+  for (int c = 0; c < D; ++c) acc[c] = 0.f;
+  float m = kNegInf, l = 0.f;
+  const float* kb = static_cast<const float*>(p.k) + kvh * p.stride_head;
+  const float* vb = static_cast<const float*>(p.v) + kvh * p.stride_head;
+  for (int j = lane; j <= lim; j += 64) {
+    const int64_t slot = static_cast<int64_t>(bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
+    const float* kr = kb + slot * p.stride_slot;
+    const float* vr = vb + slot * p.stride_slot;
+    float dot = 0.f;
+#pragma unroll
+    for (int c = 0; c < D; c += 4) {
+      const float4 t = *reinterpret_cast<const float4*>(kr + c);
+      dot = fmaf(qv[c], t.x, dot); dot = fmaf(qv[c + 1], t.y, dot);
+      dot = fmaf(qv[c + 2], t.z, dot); dot = fmaf(qv[c + 3], t.w, dot);
+    }
+    const float sc = dot * p.scale;
+    const float m_new = fmaxf(m, sc);
+    const float a = expf(m - m_new);            // exp(-inf) = 0 on the first key
+    const float w = expf(sc - m_new);
+    l = fmaf(l, a, w);
+#pragma unroll
+    for (int c = 0; c < D; c += 4) {
+      const float4 t = *reinterpret_cast<const float4*>(vr + c);
+      acc[c] = fmaf(acc[c], a, w * t.x); acc[c + 1] = fmaf(acc[c + 1], a, w * t.y);
+      acc[c + 2] = fmaf(acc[c + 2], a, w * t.z); acc[c + 3] = fmaf(acc[c + 3], a, w * t.w);
+    }
+    m = m_new;
+  }
+  // merge the 64 per-lane partial results
+  float m_all = m;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m_all = fmaxf(m_all, __shfl_xor(m_all, off));
+  const float w = m == kNegInf ? 0.f : expf(m - m_all);
+  float l_all = l * w;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) l_all += __shfl_xor(l_all, off);
+  const float inv = 1.f / l_all;
+  float* orow = static_cast<float*>(p.out) + (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
+#pragma unroll
+  for (int c = 0; c < D; ++c) {
+    float t = acc[c] * w;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off);
+    if (lane == (c & 63)) orow[c] = t * inv;
+  }
+}
+
+}  // namespace
+
+extern "C" size_t cs_window_prefill_attn_workspace(int64_t n_q, int32_t n_streams, int32_t n_q_heads,
+                                                   int32_t n_kv_heads, int32_t head_dim, int32_t dtype) {
+  (void)n_q; (void)n_streams; (void)n_q_heads; (void)n_kv_heads; (void)head_dim; (void)dtype;
+  return 0;
+}
+
+extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void* v_cache_layer,
+                                      const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
+                                      const int32_t* block_table, int32_t max_blocks, int32_t block_size,
+                                      void* out, int64_t n_q, int32_t n_streams, int32_t n_q_heads,
+                                      int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
+                                      int64_t stride_head, float softmax_scale, int32_t dtype,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (n_q < 0 || n_streams < 0 || n_q_heads < 1 || n_kv_heads < 1 || max_blocks < 0) return CS_EINVAL;
+  if (stride_slot < 0 || stride_head < 0) return CS_EINVAL;
+  if (n_q_heads % n_kv_heads) return CS_EINVAL;
+  if (dtype != CS_F32 && dtype != CS_BF16) return CS_EUNSUPPORTED;
+  if (head_dim != 64 && head_dim != 128) return CS_EUNSUPPORTED;
+  if (block_size != CS_KV_BLOCK) return CS_EUNSUPPORTED;
+  const int group = n_q_heads / n_kv_heads;
+  if (group > 16) return CS_EUNSUPPORTED;
+  const int elems = dtype == CS_BF16 ? 8 : 4;
+  if (stride_slot % elems || stride_head % elems) return CS_EUNSUPPORTED;
+  if (n_q == 0 || n_streams == 0) return CS_OK;
+  if (!q || !k_cache_layer || !v_cache_layer || !cu_q || !q_pos || !kv_len || !block_table || !out)
+    return CS_EINVAL;
+  if (!cs::aligned16(q) || !cs::aligned16(out) || !cs::aligned16(k_cache_layer) ||
+      !cs::aligned16(v_cache_layer))
+    return CS_EUNSUPPORTED;
+  if (n_q * n_q_heads >= (1ll << 31)) return CS_EUNSUPPORTED;
+
+  AttnParams p;
+  p.q = q;
+  p.k = k_cache_layer;
+  p.v = v_cache_layer;
+  p.out = out;
+  p.cu_q = cu_q;
+  p.q_pos = q_pos;
+  p.block_table = block_table;
+  p.stride_slot = stride_slot;
+  p.stride_head = stride_head;
+  p.max_blocks = max_blocks;
+  p.n_streams = n_streams;
+  p.n_q_heads = n_q_heads;
+  p.n_kv_heads = n_kv_heads;
+  p.group = group;
+  p.scale = softmax_scale;
+  p.scale_log2e = softmax_scale * 1.4426950408889634f;
+  p.n_q = n_q;
+  hipStream_t st = cs::as_stream(stream);
+  if (dtype == CS_BF16) {
+    // upper bound on the number of row tiles: sum_s ceil(n_q_s * group / 128)
+    const int64_t tiles = (n_q * group) / kBM + n_streams;
+    if (tiles > 0x7fffffffll) return CS_EUNSUPPORTED;
+    const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_kv_heads));
+    if (head_dim == 128)
+      hipLaunchKernelGGL(window_attn_bf16_kernel<128>, grid, dim3(256), 0, st, p);
+    else
+      hipLaunchKernelGGL(window_attn_bf16_kernel<64>, grid, dim3(256), 0, st, p);
+  } else {
+    const int64_t units = n_q * n_q_heads;
+    const dim3 grid(static_cast<unsigned>((units + 3) / 4));
+    if (head_dim == 128)
+      hipLaunchKernelGGL(window_attn_f32_kernel<128>, grid, dim3(256), 0, st, p);
+    else
+      hipLaunchKernelGGL(window_attn_f32_kernel<64>, grid, dim3(256), 0, st, p);
+  }
+  return cs::note_hip(hipGetLastError());
+}

@@ -1,0 +1,228 @@
+"""Drives one slide step of a batch of streams through the four device calls.
+
+`assemble_step` builds everything a step needs from a synthetic workload (history scoring to get
+the cached window's token layout, the step's own scoring, block tables, the refresh plan, and the
+Q/K/V tensors); `DeviceStep` holds those inputs on the GPU and issues the calls in the order the
+method prescribes: score+compact, re-rotate (all layers), then per layer refresh write followed by
+attention (paper Sec. 3.5: planning first, KV-context preparation next, joint prefill last).
+
+The scoring function is a parameter so that the same assembly can be driven by the HIP kernels
+(`hip_scorer`, the product path) or, in tests, by the CPU oracle; nothing here falls back to a CPU
+implementation on its own.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Callable, Optional
+
+import numpy as np
+
+from . import planner, synth
+
+
+# scorer(mv, sad, frame_type, cu_frames, acc, workload, tau_mv_sq, tau_sad) ->
+#     (keep [F,T] uint8, kept_idx int32, kept_off int32 [F+1], acc_out [B,P] uint8)
+Scorer = Callable[..., tuple]
+
+
+def hip_scorer(mv, sad, frame_type, cu_frames, acc, w: synth.Workload, tau_mv_sq: int, tau_sad: int):
+    """cs_score_compact on NumPy inputs (copies in, copies out).  Product path: HIP only."""
+    import torch
+    from . import binding as cs
+    dev = torch.device("cuda")
+    n_frames, n_streams = int(frame_type.shape[0]), int(cu_frames.shape[0]) - 1
+    t_per = w.tokens_per_frame
+    d_mv = torch.from_numpy(mv).to(dev)
+    d_sad = torch.from_numpy(sad.view(np.int32)).to(dev) if w.use_residual else None
+    d_ft = torch.from_numpy(frame_type).to(dev)
+    d_cu = torch.from_numpy(cu_frames).to(dev)
+    d_acc = torch.from_numpy(acc).to(dev) if acc is not None else None
+    keep = torch.empty((n_frames, t_per), dtype=torch.uint8, device=dev)
+    idx = torch.empty((max(1, n_frames * t_per),), dtype=torch.int32, device=dev)
+    off = torch.empty((n_frames + 1,), dtype=torch.int32, device=dev)
+    ws_bytes = cs.cs_score_compact_workspace(n_streams, n_frames, w.grid_h, w.grid_w, w.group)
+    ws = torch.empty((max(8, ws_bytes),), dtype=torch.uint8, device=dev)
+    cs.cs_score_compact(d_mv, d_sad, None, d_ft, d_cu, d_acc, n_streams, n_frames, w.grid_h, w.grid_w,
+                        w.group, tau_mv_sq, tau_sad, w.use_residual, keep, idx, off, ws, ws_bytes)
+    torch.cuda.synchronize()
+    off_h = off.cpu().numpy()
+    return (keep.cpu().numpy(), idx[: int(off_h[-1])].cpu().numpy(), off_h,
+            None if d_acc is None else d_acc.cpu().numpy())
+
+
+@dataclass
+class StepData:
+    """Inputs of one slide step.  Small arrays are NumPy on the host; big tensors are torch."""
+    workload: synth.Workload
+    # (a) the S new frames of every stream, stream-major
+    mv: np.ndarray
+    sad: np.ndarray
+    frame_type: np.ndarray
+    cu_frames: np.ndarray
+    acc_in: np.ndarray                 # accumulated mask carried in from the history
+    # layouts and plan
+    old_layout: planner.WindowLayout
+    plan: planner.StepPlan
+    n_slots: int
+    # tensors (torch): pool [L, n_slots, Hkv, d]; q [L, n_q, Hq, d]; k_new, v_new [L, n_q, Hkv, d]
+    k_pool: object = None
+    v_pool: object = None
+    q: object = None
+    k_new: object = None
+    v_new: object = None
+    softmax_scale: float = 0.0
+    info: dict = field(default_factory=dict)
+
+
+def assemble_step(w: synth.Workload, scorer: Scorer, device="cpu", with_tensors: bool = True) -> StepData:
+    """History -> cached window layout -> this step's scoring -> block tables -> refresh plan."""
+    meta = synth.batch_metadata(w)
+    n_streams, hist, stride, window = w.n_streams, w.history, w.stride, w.window
+    t_per = w.tokens_per_frame
+
+    # 1. history (everything before the new frames), accumulated mask starting from zero
+    past = hist - stride
+    rows = meta.rows(0, past)
+    cu = (np.arange(n_streams + 1) * past).astype(np.int32)
+    acc0 = np.zeros((n_streams, w.patches), np.uint8)
+    keep_h, _, off_h, acc_h = scorer(meta.mv[rows], meta.sad[rows], meta.frame_type[rows], cu, acc0, w,
+                                     w.tau_mv_sq, w.tau_sad)
+    counts_h = np.diff(off_h).reshape(n_streams, past)
+    old_counts = counts_h[:, past - window:].astype(np.int32)
+    if w.dense_history:
+        old_counts = np.full_like(old_counts, t_per)          # cache holds unpruned rows
+    old_types = meta.frame_type.reshape(n_streams, hist)[:, past - window: past]
+
+    # 2. this step: the S new frames of every stream
+    rows_new = meta.rows(past, stride)
+    cu_new = (np.arange(n_streams + 1) * stride).astype(np.int32)
+    keep_n, _, off_n, _ = scorer(meta.mv[rows_new], meta.sad[rows_new], meta.frame_type[rows_new], cu_new,
+                                 acc_h.copy(), w, w.tau_mv_sq, w.tau_sad)
+    new_counts = np.diff(off_n).reshape(n_streams, stride).astype(np.int32)
+    new_types = meta.frame_type[rows_new].reshape(n_streams, stride)
+
+    # 3. block tables: old and new windows draw distinct blocks from one pool
+    old_len = old_counts.sum(axis=1) + w.n_text
+    new_len = old_counts[:, stride:].sum(axis=1) + new_counts.sum(axis=1) + w.n_text
+    nb_old, nb_new = planner.blocks_needed(old_len), planner.blocks_needed(new_len)
+    ids = synth.block_ids(w, int(nb_old.sum() + nb_new.sum()))
+    max_blocks = int(max(nb_old.max(), nb_new.max()))
+    bt_old = np.zeros((n_streams, max_blocks), np.int32)
+    bt_new = np.zeros((n_streams, max_blocks), np.int32)
+    at = 0
+    for s in range(n_streams):
+        bt_old[s, : nb_old[s]] = ids[at: at + nb_old[s]]
+        at += int(nb_old[s])
+        bt_new[s, : nb_new[s]] = ids[at: at + nb_new[s]]
+        at += int(nb_new[s])
+    n_slots = int(ids.shape[0]) * synth.KV_BLOCK
+
+    # 4. plan
+    old_layout = planner.WindowLayout(old_types.astype(np.uint8), old_counts, w.n_text, bt_old)
+    plan = planner.plan_slide(old_layout, new_types, new_counts, bt_new, t_per)
+
+    data = StepData(w, meta.mv[rows_new], meta.sad[rows_new], meta.frame_type[rows_new], cu_new, acc_h,
+                    old_layout, plan, n_slots, softmax_scale=1.0 / math.sqrt(w.head_dim))
+    n_q = int(plan.q_pos.shape[0])
+    vis = float(plan.kv_len.sum())
+    pairs = float((plan.q_pos.astype(np.int64) + 1).sum())
+    data.info = dict(n_q=n_q, n_reuse=int(plan.src_slot.shape[0]), kv_len_total=int(vis),
+                     visible_pairs=pairs, n_slots=n_slots,
+                     kept_new=int(new_counts.sum()), reused_fraction=float(plan.src_slot.shape[0]) / max(1.0, vis))
+    if with_tensors:
+        shape_pool = (w.n_layers, n_slots, w.n_kv_heads, w.head_dim)
+        data.k_pool = synth.normal_tensor(w, (1,), shape_pool, device)
+        data.v_pool = synth.normal_tensor(w, (2,), shape_pool, device)
+        data.q = synth.normal_tensor(w, (3,), (w.n_layers, n_q, w.n_q_heads, w.head_dim), device)
+        data.k_new = synth.normal_tensor(w, (4,), (w.n_layers, n_q, w.n_kv_heads, w.head_dim), device)
+        data.v_new = synth.normal_tensor(w, (5,), (w.n_layers, n_q, w.n_kv_heads, w.head_dim), device)
+    return data
+
+
+class DeviceStep:
+    """A step resident on the GPU; each method enqueues exactly one C-ABI call."""
+
+    def __init__(self, data: StepData):
+        import torch
+        from . import binding as cs
+        self.cs = cs
+        self.data = data
+        w = data.workload
+        dev = torch.device("cuda")
+        self.dev = dev
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        self.dtype = cs.CS_BF16 if w.dtype == "bf16" else cs.CS_F32
+        # (a)
+        self.mv = to(data.mv)
+        self.sad = to(data.sad.view(np.int32)) if w.use_residual else None
+        self.frame_type = to(data.frame_type)
+        self.cu_frames = to(data.cu_frames)
+        self.acc = to(data.acc_in)
+        self.n_frames = int(data.frame_type.shape[0])
+        t_per = w.tokens_per_frame
+        self.keep = torch.zeros((self.n_frames, t_per), dtype=torch.uint8, device=dev)
+        self.kept_idx = torch.zeros((self.n_frames * t_per,), dtype=torch.int32, device=dev)
+        self.kept_off = torch.zeros((self.n_frames + 1,), dtype=torch.int32, device=dev)
+        self.ws_a_bytes = cs.cs_score_compact_workspace(w.n_streams, self.n_frames, w.grid_h, w.grid_w, w.group)
+        self.ws_a = torch.zeros((max(8, self.ws_a_bytes),), dtype=torch.uint8, device=dev)
+        # (b)
+        p = data.plan
+        self.src_slot, self.dst_slot, self.delta = to(p.src_slot), to(p.dst_slot), to(p.delta)
+        self.k_pool = data.k_pool.to(dev)
+        self.v_pool = data.v_pool.to(dev)
+        self.stride_layer = self.k_pool.stride(0)
+        self.stride_slot = self.k_pool.stride(1)
+        self.stride_head = self.k_pool.stride(2)
+        # (c), (d)
+        self.q_slot, self.q_pos = to(p.q_slot), to(p.q_pos)
+        self.cu_q, self.kv_len = to(p.cu_q), to(p.kv_len)
+        self.block_table = to(p.layout.block_table)
+        self.max_blocks = int(p.layout.block_table.shape[1])
+        self.q = data.q.to(dev)
+        self.k_new = data.k_new.to(dev)
+        self.v_new = data.v_new.to(dev)
+        self.out = torch.zeros_like(self.q)
+        self.n_q = int(p.q_pos.shape[0])
+        ws_d = cs.cs_window_prefill_attn_workspace(self.n_q, w.n_streams, w.n_q_heads, w.n_kv_heads,
+                                                   w.head_dim, self.dtype)
+        self.ws_d_bytes = ws_d
+        self.ws_d = torch.zeros((max(8, ws_d),), dtype=torch.uint8, device=dev)
+
+    def score_compact(self):
+        w = self.data.workload
+        self.cs.cs_score_compact(self.mv, self.sad, None, self.frame_type, self.cu_frames, self.acc,
+                                 w.n_streams, self.n_frames, w.grid_h, w.grid_w, w.group, w.tau_mv_sq,
+                                 w.tau_sad, w.use_residual, self.keep, self.kept_idx, self.kept_off,
+                                 self.ws_a, self.ws_a_bytes)
+
+    def rerotate(self, in_place: bool = False):
+        w = self.data.workload
+        self.cs.cs_kv_rerotate(self.k_pool, None if in_place else self.v_pool, self.src_slot,
+                               None if in_place else self.dst_slot, self.delta,
+                               int(self.src_slot.shape[0]), w.n_layers, w.n_kv_heads, w.head_dim,
+                               self.stride_layer, self.stride_slot, self.stride_head, w.rope_base,
+                               self.cs.CS_ROPE_HALF_SPLIT, self.dtype)
+
+    def refresh_scatter(self, layer: int):
+        w = self.data.workload
+        self.cs.cs_kv_refresh_scatter(self.k_new[layer], self.v_new[layer], self.q_slot,
+                                      self.k_pool[layer], self.v_pool[layer], self.n_q, w.n_kv_heads,
+                                      w.head_dim, self.stride_slot, self.stride_head, self.dtype)
+
+    def attention(self, layer: int):
+        w = self.data.workload
+        self.cs.cs_window_prefill_attn(self.q[layer], self.k_pool[layer], self.v_pool[layer], self.cu_q,
+                                       self.q_pos, self.kv_len, self.block_table, self.max_blocks,
+                                       self.cs.CS_KV_BLOCK, self.out[layer], self.n_q, w.n_streams,
+                                       w.n_q_heads, w.n_kv_heads, w.head_dim, self.stride_slot,
+                                       self.stride_head, self.data.softmax_scale, self.dtype,
+                                       self.ws_d if self.ws_d_bytes else None, self.ws_d_bytes)
+
+    def run(self):
+        """One pass of the whole hot path."""
+        self.score_compact()
+        self.rerotate()
+        for layer in range(self.data.workload.n_layers):
+            self.refresh_scatter(layer)
+            self.attention(layer)

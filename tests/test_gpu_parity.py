@@ -1,0 +1,510 @@
+"""GPU-vs-oracle parity through the C ABI (needs an MI355X: `-m gpu`).
+
+Integer / byte / index results must match bit for bit; re-rotated keys within 1e-2 max-abs and
+attention within 2e-2 max-abs, 1e-2 mean-relative of the float64 oracle (see tests/helpers.py).
+Every case prints what it is about to run before touching the GPU.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import codecsight_oracle as oc
+from paper_2604_06036_amd import engine, planner, synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def cs():
+    from paper_2604_06036_amd import binding
+    say(f"library: {binding.cs_version()} on {torch.cuda.get_device_name(0)}")
+    return binding
+
+
+# =============================================================================== (a) scoring
+def _score_gpu(cs, mv, sad, intra, ft, cu, acc, gh, gw, g, tmv, tsad, use_res):
+    n_frames, n_streams = int(ft.shape[0]), int(cu.shape[0]) - 1
+    t_per = (gh // g) * (gw // g)
+    d = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    d_acc = d(acc)
+    keep = torch.full((max(1, n_frames), t_per), 9, dtype=torch.uint8, device=DEV)
+    idx = torch.full((max(1, n_frames * t_per),), -7, dtype=torch.int32, device=DEV)
+    off = torch.full((n_frames + 1,), -7, dtype=torch.int32, device=DEV)
+    nbytes = cs.cs_score_compact_workspace(n_streams, n_frames, gh, gw, g)
+    ws = torch.randint(0, 255, (max(8, nbytes),), dtype=torch.uint8, device=DEV)   # dirty workspace
+    cs.cs_score_compact(d(mv), d(None if sad is None else sad.view(np.int32)), d(intra), d(ft), d(cu),
+                        d_acc, n_streams, n_frames, gh, gw, g, tmv, tsad, use_res, keep, idx, off, ws, nbytes)
+    torch.cuda.synchronize()
+    if n_streams > 0 and n_frames > 0:
+        assert int(ws[4:8].view(torch.int32).item()) == 0, "look-back wait ran into its bound"
+    return (keep.cpu().numpy()[:n_frames], idx.cpu().numpy(), off.cpu().numpy(),
+            None if d_acc is None else d_acc.cpu().numpy())
+
+
+def _score_case(cs, rng, n_streams, frames_per_stream, gh, gw, g, tmv, tsad, use_res, with_acc,
+                with_intra, p_iframe=0.15, spread=12):
+    counts = np.asarray(frames_per_stream, np.int32)
+    cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    n_frames, n_patch = int(cu[-1]), gh * gw
+    mv = np.rint(rng.normal(0, spread, size=(n_frames, n_patch, 2))).astype(np.int16)
+    sad = rng.integers(0, 1200, size=(n_frames, n_patch), dtype=np.uint32)
+    ft = (rng.random(n_frames) < p_iframe).astype(np.uint8)
+    intra = (rng.random((n_frames, n_patch)) < 0.02).astype(np.uint8) * 3 if with_intra else None
+    acc = (rng.random((n_streams, n_patch)) < 0.1).astype(np.uint8) if with_acc else None
+    want = oc.score_compact(mv, sad if use_res else None, intra, ft, cu, acc, gh, gw, g, tmv, tsad, use_res)
+    got = _score_gpu(cs, mv, sad if use_res else None, intra, ft, cu, acc, gh, gw, g, tmv, tsad, use_res)
+    keep_w, idx_w, off_w, acc_w = want
+    keep_g, idx_g, off_g, acc_g = got
+    assert np.array_equal(keep_g, keep_w)
+    assert np.array_equal(off_g, off_w)
+    assert np.array_equal(idx_g[: idx_w.size], idx_w)
+    assert np.all(idx_g[idx_w.size:] == -7)                      # the tail is left untouched
+    if with_acc:
+        assert np.array_equal(acc_g != 0, acc_w != 0)
+    return int(idx_w.size)
+
+
+SCORE_CASES = [
+    # streams, frames per stream,            grid,     g, tmv, tsad, res,  acc,  intra
+    (1, [1], (16, 16), 1, 17, 401, True, True, False),
+    (1, [4], (16, 16), 1, 17, 401, True, False, False),
+    (3, [2, 0, 5], (16, 16), 1, 100, 600, True, True, True),       # a stream with no frames
+    (5, [1, 1, 1, 1, 1], (26, 46), 1, 150, 900, True, True, False),  # T = 1196: ragged sweeps
+    (9, [3] * 9, (7, 9), 1, 60, 500, False, True, True),           # T = 63 < one wave
+    (4, [2, 3, 1, 2], (32, 32), 2, 200, 800, True, True, True),     # 2x2 projection groups
+    (2, [2, 2], (6, 10), 2, 90, 300, True, False, False),
+    (37, [1] * 37, (16, 16), 1, 300, 1000, True, True, False),     # 10 tiles of 4 streams
+    (301, list(np.random.default_rng(5).integers(0, 4, 301)), (8, 8), 1, 250, 900, True, True, False),
+    (2, [3, 3], (16, 16), 1, 0, 0, True, True, False),              # zero thresholds: keep all
+    (2, [3, 3], (16, 16), 1, 0xFFFFFFFF, 0xFFFFFFFF, True, False, False),   # nothing kept
+]
+
+
+@pytest.mark.parametrize("case", range(len(SCORE_CASES)))
+def test_score_compact_random(cs, case):
+    n_streams, fps, (gh, gw), g, tmv, tsad, res, acc, intra = SCORE_CASES[case]
+    say(f"score_compact case {case}: streams={n_streams} frames={sum(fps)} grid={gh}x{gw} g={g} "
+        f"tau=({tmv},{tsad}) res={res} acc={acc} intra={intra}")
+    rng = np.random.default_rng(1000 + case)
+    p_i = 0.0 if tmv == 0xFFFFFFFF else 0.15
+    kept = _score_case(cs, rng, n_streams, fps, gh, gw, g, tmv, tsad, res, acc, intra, p_iframe=p_i)
+    if tmv == 0:
+        assert kept == sum(fps) * (gh // g) * (gw // g)
+    if tmv == 0xFFFFFFFF:
+        assert kept == 0
+
+
+def test_score_compact_empty_batch(cs):
+    say("score_compact: zero frames / zero streams")
+    off = torch.full((1,), -5, dtype=torch.int32, device=DEV)
+    cs.cs_score_compact(None, None, None, None, None, None, 0, 0, 16, 16, 1, 17, 401, False, None, None,
+                        off, None, 0)
+    torch.cuda.synchronize()
+    assert off.cpu().tolist() == [0]
+
+
+def test_score_compact_many_tiles(cs):
+    # 4096 streams x 1 frame x 256 tokens: 1024 tiles chained by the look-back
+    say("score_compact: 4096 streams, 1024 look-back tiles")
+    rng = np.random.default_rng(77)
+    _score_case(cs, rng, 4096, [1] * 4096, 16, 16, 1, 400, 1100, True, True, False, p_iframe=0.1)
+
+
+def test_score_compact_i_frame_ignores_metadata(cs):
+    say("score_compact: garbage in I-frame metadata")
+    rng = np.random.default_rng(3)
+    n_patch = 256
+    ft = np.array([1, 0, 1, 0], np.uint8)
+    cu = np.array([0, 2, 4], np.int32)
+    mv = np.rint(rng.normal(0, 3, size=(4, n_patch, 2))).astype(np.int16)
+    sad = rng.integers(0, 500, size=(4, n_patch), dtype=np.uint32)
+    acc = np.ones((2, n_patch), np.uint8)
+    a = _score_gpu(cs, mv, sad, None, ft, cu, acc, 16, 16, 1, 17, 401, True)
+    mv[[0, 2]] = 32767
+    sad[[0, 2]] = 0xFFFFFFFF
+    b = _score_gpu(cs, mv, sad, None, ft, cu, acc, 16, 16, 1, 17, 401, True)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    assert a[0][0].all() and a[0][2].all()
+
+
+# =============================================================================== (b) re-rotation
+def _pool(rng, shape, dtype):
+    x = torch.from_numpy(rng.normal(size=shape).astype(np.float32))
+    return x if dtype == "f32" else x.to(torch.bfloat16)
+
+
+REROT_CASES = [
+    # dtype, L, n_slots, Hkv, d, n_rows, style, repack, base, layout
+    ("f32", 1, 512, 1, 64, 120, 0, True, 1e4, "lshd"),
+    ("f32", 3, 256, 2, 128, 77, 1, False, 1e6, "lshd"),
+    ("bf16", 28, 1024, 4, 128, 490, 0, True, 1e6, "lshd"),
+    ("bf16", 5, 640, 8, 128, 333, 0, False, 1e6, "lshd"),
+    ("bf16", 2, 640, 3, 64, 200, 1, True, 1e4, "lshd"),
+    ("bf16", 7, 640, 4, 128, 250, 0, True, 1e6, "lhsd"),       # head-major pool: stride_head != d
+    ("bf16", 9, 300, 2, 256, 100, 0, True, 5e5, "lshd"),
+    ("bf16", 1, 64, 1, 16, 1, 0, True, 1e4, "lshd"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(REROT_CASES)))
+def test_kv_rerotate(cs, case):
+    dtype, n_layers, n_slots, n_heads, d, n_rows, style, repack, base, layout = REROT_CASES[case]
+    say(f"kv_rerotate case {case}: {dtype} L={n_layers} slots={n_slots} Hkv={n_heads} d={d} rows={n_rows} "
+        f"style={style} repack={repack} layout={layout}")
+    rng = np.random.default_rng(2000 + case)
+    if layout == "lshd":
+        k = _pool(rng, (n_layers, n_slots, n_heads, d), dtype)
+        v = _pool(rng, (n_layers, n_slots, n_heads, d), dtype)
+        view = lambda t: t
+    else:
+        k = _pool(rng, (n_layers, n_heads, n_slots, d), dtype)
+        v = _pool(rng, (n_layers, n_heads, n_slots, d), dtype)
+        view = lambda t: t.permute(0, 2, 1, 3)                  # logical [L, slot, head, d]
+    assert (2 if repack else 1) * n_rows <= n_slots, "case needs disjoint source and destination slots"
+    perm = rng.permutation(n_slots)
+    src = perm[:n_rows].astype(np.int32)
+    dst = perm[n_rows: 2 * n_rows].astype(np.int32) if repack else None
+    delta = rng.integers(-2392, 2393, size=n_rows).astype(np.int32)
+    delta[: min(3, n_rows)] = [0, -256, 2392][: min(3, n_rows)]
+
+    k_ref, v_ref = oc.rerotate(hp.f64(view(k)), hp.f64(view(v)), src, dst, delta, base, style)
+
+    kd, vd = k.to(DEV), v.to(DEV)
+    kv_, vv_ = view(kd), view(vd)
+    cs.cs_kv_rerotate(kd, vd if repack else None, torch.from_numpy(src).to(DEV),
+                      torch.from_numpy(dst).to(DEV) if repack else None, torch.from_numpy(delta).to(DEV),
+                      n_rows, n_layers, n_heads, d, kv_.stride(0), kv_.stride(1), kv_.stride(2), base, style,
+                      cs.CS_BF16 if dtype == "bf16" else cs.CS_F32)
+    torch.cuda.synchronize()
+    k_out, v_out = view(kd.cpu()), view(vd.cpu())
+    tgt = dst if repack else src
+    got_rows = k_out[:, torch.from_numpy(tgt.astype(np.int64))].permute(1, 0, 2, 3).contiguous()
+    stats = hp.check_rerotated(got_rows, k_ref, dtype)
+    say(f"  -> {stats}")
+    if repack:                                                   # values copied bit for bit
+        assert torch.equal(v_out[:, torch.from_numpy(dst.astype(np.int64))],
+                           view(v)[:, torch.from_numpy(src.astype(np.int64))])
+    # every other row of the pool is bit-unchanged
+    other = np.setdiff1d(np.arange(n_slots), tgt)
+    oi = torch.from_numpy(other)
+    assert torch.equal(k_out[:, oi], view(k)[:, oi]) and torch.equal(v_out[:, oi], view(v)[:, oi])
+    if not repack:
+        assert torch.equal(v_out, view(v))
+
+
+def test_kv_rerotate_closed_form_on_gpu(cs):
+    """Keys cached at p_old, corrected by delta, equal keys computed at p_old + delta (Eq. 6)."""
+    say("kv_rerotate: closed form R(delta) R(p) k == R(p + delta) k, fp32 storage")
+    rng = np.random.default_rng(42)
+    n, d, base = 300, 128, 1e6
+    k_raw = rng.normal(size=(n, d))
+    p_old = rng.integers(0, 20001, size=n)
+    delta = rng.integers(-2392, 2393, size=n).astype(np.int32)
+    cached = torch.from_numpy(oc.rotate(k_raw, p_old, base).astype(np.float32)).reshape(1, n, 1, d).to(DEV)
+    cs.cs_kv_rerotate(cached, None, torch.arange(n, dtype=torch.int32, device=DEV), None,
+                      torch.from_numpy(delta).to(DEV), n, 1, 1, d, n * d, d, d, base, 0, cs.CS_F32)
+    torch.cuda.synchronize()
+    want = oc.rotate(k_raw, p_old + delta, base)
+    assert np.abs(hp.f64(cached.reshape(n, d)) - want).max() <= 2e-5
+
+
+# =============================================================================== (c) scatter
+@pytest.mark.parametrize("dtype,n_tok,n_heads,d,layout", [
+    ("f32", 332, 1, 64, "shd"), ("bf16", 425, 4, 128, "shd"), ("bf16", 1000, 8, 128, "hsd"),
+    ("bf16", 1, 2, 64, "shd"), ("f32", 63, 3, 128, "shd")])
+def test_kv_refresh_scatter(cs, dtype, n_tok, n_heads, d, layout):
+    say(f"kv_refresh_scatter: {dtype} tokens={n_tok} Hkv={n_heads} d={d} layout={layout}")
+    rng = np.random.default_rng(n_tok * 7 + d)
+    n_slots = 2 * n_tok + 40
+    shape = (n_slots, n_heads, d) if layout == "shd" else (n_heads, n_slots, d)
+    view = (lambda t: t) if layout == "shd" else (lambda t: t.permute(1, 0, 2))
+    kc, vc = _pool(rng, shape, dtype), _pool(rng, shape, dtype)
+    kn, vn = _pool(rng, (n_tok, n_heads, d), dtype), _pool(rng, (n_tok, n_heads, d), dtype)
+    slot = rng.permutation(n_slots)[:n_tok].astype(np.int32)
+    slot[rng.random(n_tok) < 0.1] = -1
+    raw = torch.int16 if dtype == "bf16" else torch.int32
+    k_want = view(kc).contiguous().view(raw).numpy().copy()
+    v_want = view(vc).contiguous().view(raw).numpy().copy()
+    oc.scatter(k_want, kn.view(raw).numpy(), slot)
+    oc.scatter(v_want, vn.view(raw).numpy(), slot)
+    kd, vd = kc.to(DEV), vc.to(DEV)
+    cs.cs_kv_refresh_scatter(kn.to(DEV), vn.to(DEV), torch.from_numpy(slot).to(DEV), kd, vd, n_tok, n_heads,
+                             d, view(kd).stride(0), view(kd).stride(1),
+                             cs.CS_BF16 if dtype == "bf16" else cs.CS_F32)
+    torch.cuda.synchronize()
+    assert np.array_equal(view(kd.cpu()).contiguous().view(raw).numpy(), k_want)
+    assert np.array_equal(view(vd.cpu()).contiguous().view(raw).numpy(), v_want)
+
+
+# =============================================================================== (d) attention
+def _attn_case(cs, rng, dtype, n_q_heads, n_kv_heads, d, kv_lens, n_qs, shuffle=True, poison=True,
+               all_queries=False):
+    n_streams = len(kv_lens)
+    nb = [(-(-L // 16)) for L in kv_lens]
+    max_blocks = max(nb) + 1
+    n_blocks = sum(nb) + 3
+    ids = rng.permutation(n_blocks) if shuffle else np.arange(n_blocks)
+    bt = np.full((n_streams, max_blocks), 0, np.int32)
+    at = 0
+    for s in range(n_streams):
+        bt[s, : nb[s]] = ids[at: at + nb[s]]
+        at += nb[s]
+    kc = _pool(rng, (n_blocks * 16, n_kv_heads, d), dtype)
+    vc = _pool(rng, (n_blocks * 16, n_kv_heads, d), dtype)
+    q_pos, cu = [], [0]
+    for s in range(n_streams):
+        if all_queries:
+            pos = np.arange(kv_lens[s])
+        else:
+            pos = np.sort(rng.choice(kv_lens[s], size=n_qs[s], replace=False)) if n_qs[s] else np.zeros(0, int)
+        q_pos.append(pos)
+        cu.append(cu[-1] + pos.size)
+    q_pos = np.concatenate(q_pos).astype(np.int32)
+    cu = np.asarray(cu, np.int32)
+    n_q = int(q_pos.size)
+    q = _pool(rng, (max(1, n_q), n_q_heads, d), dtype)[:n_q]
+    scale = 1.0 / math.sqrt(d)
+    ref = oc.window_attn(hp.f64(q), hp.f64(kc), hp.f64(vc), cu, q_pos, bt, n_q_heads, scale)
+    if poison:
+        # cache rows past every stream's frontier hold NaN: they must never influence a result
+        used = np.zeros(n_blocks * 16, bool)
+        for s in range(n_streams):
+            seg = q_pos[cu[s]: cu[s + 1]]
+            if seg.size:
+                j = np.arange(int(seg.max()) + 1)
+                used[bt[s, j // 16] * 16 + j % 16] = True
+        kc[torch.from_numpy(~used)] = float("nan")
+        vc[torch.from_numpy(~used)] = float("nan")
+    out = torch.full((max(1, n_q), n_q_heads, d), 7.0, dtype=q.dtype, device=DEV)
+    kd, vd = kc.to(DEV), vc.to(DEV)
+    code = cs.CS_BF16 if dtype == "bf16" else cs.CS_F32
+    wsb = cs.cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, d, code)
+    ws = torch.zeros((max(8, wsb),), dtype=torch.uint8, device=DEV)
+    cs.cs_window_prefill_attn(q.to(DEV), kd, vd, torch.from_numpy(cu).to(DEV), torch.from_numpy(q_pos).to(DEV),
+                              torch.tensor(kv_lens, dtype=torch.int32, device=DEV),
+                              torch.from_numpy(bt).to(DEV), max_blocks, 16, out, n_q, n_streams, n_q_heads,
+                              n_kv_heads, d, kd.stride(0), kd.stride(1), scale, code, ws, wsb)
+    torch.cuda.synchronize()
+    return hp.check_attention(out[:n_q].cpu(), ref, dtype)
+
+
+ATTN_CASES = [
+    # dtype, Hq, Hkv, d, kv_lens, n_qs
+    ("f32", 2, 1, 64, [452], [332]),
+    ("f32", 4, 2, 128, [100, 37], [20, 37]),
+    ("bf16", 28, 4, 128, [915], [425]),                       # 7 query heads per kv head
+    ("bf16", 32, 8, 128, [300, 1, 640, 77], [100, 1, 333, 0]),  # a stream with no queries, one of length 1
+    ("bf16", 4, 4, 64, [200, 129], [64, 129]),                # MHA, d = 64
+    ("bf16", 8, 1, 128, [513], [70]),                         # 8-way group, ragged tail of one key
+    ("bf16", 2, 1, 64, [1040], [18]),
+    ("bf16", 28, 4, 128, [64, 65, 127, 128], [5, 9, 19, 37]),  # frontiers on tile edges
+]
+
+
+@pytest.mark.parametrize("case", range(len(ATTN_CASES)))
+def test_window_prefill_attn(cs, case):
+    dtype, hq, hkv, d, kv_lens, n_qs = ATTN_CASES[case]
+    say(f"window_prefill_attn case {case}: {dtype} heads={hq}/{hkv} d={d} kv={kv_lens} n_q={n_qs}")
+    stats = _attn_case(cs, np.random.default_rng(3000 + case), dtype, hq, hkv, d, kv_lens, n_qs)
+    say(f"  -> {stats}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_nothing_pruned_equals_full_causal(cs, dtype):
+    """With every token a query the call is plain causal attention (1040-token tiny window)."""
+    say(f"window_prefill_attn: all 1040 tokens are queries, {dtype}")
+    stats = _attn_case(cs, np.random.default_rng(11), dtype, 2, 1, 64, [1040], [1040], all_queries=True)
+    say(f"  -> {stats}")
+
+
+def test_attention_properties_on_gpu(cs):
+    """Constant values come back unchanged; a query at index 0 returns V_0."""
+    say("window_prefill_attn: V == 1 and q_pos == 0 properties (bf16)")
+    rng = np.random.default_rng(5)
+    n_q, hq, hkv, d = 50, 8, 2, 128
+    kc = _pool(rng, (512, hkv, d), "bf16").to(DEV)
+    vc = torch.ones((512, hkv, d), dtype=torch.bfloat16, device=DEV)
+    q = _pool(rng, (n_q, hq, d), "bf16").to(DEV)
+    q_pos = torch.from_numpy(np.sort(rng.choice(500, n_q, replace=False)).astype(np.int32)).to(DEV)
+    q_pos[0] = 0
+    bt = torch.arange(32, dtype=torch.int32, device=DEV).reshape(1, 32)
+    out = torch.zeros_like(q)
+    args = (torch.tensor([0, n_q], dtype=torch.int32, device=DEV), q_pos,
+            torch.tensor([500], dtype=torch.int32, device=DEV), bt, 32, 16)
+    cs.cs_window_prefill_attn(q, kc, vc, *args, out, n_q, 1, hq, hkv, d, hkv * d, d, 0.09, cs.CS_BF16)
+    torch.cuda.synchronize()
+    assert torch.all(out.float() == 1.0)
+    vr = _pool(rng, (512, hkv, d), "bf16").to(DEV)
+    cs.cs_window_prefill_attn(q, kc, vr, *args, out, n_q, 1, hq, hkv, d, hkv * d, d, 0.09, cs.CS_BF16)
+    torch.cuda.synchronize()
+    for h in range(hq):
+        assert torch.equal(out[0, h], vr[0, h // (hq // hkv)])
+
+
+# =============================================================================== whole step
+def _oracle_step(data_o: engine.StepData, layers):
+    """b -> c -> d with oracle pieces on host copies of the inputs; returns per-layer results."""
+    w, p = data_o.workload, data_o.plan
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    k_pool, v_pool = data_o.k_pool.clone(), data_o.v_pool.clone()
+    k_rows, v_rows = oc.rerotate(hp.f64(k_pool[layers]), hp.f64(v_pool[layers]), p.src_slot, p.dst_slot,
+                                 p.delta, w.rope_base)
+    dst = torch.from_numpy(p.dst_slot.astype(np.int64))
+    outs = {}
+    for i, layer in enumerate(layers):
+        k_pool[layer][dst] = hp.round_like(k_rows[:, i], tdt)
+        v_pool[layer][dst] = hp.round_like(v_rows[:, i], tdt)
+        raw = torch.int16 if w.dtype == "bf16" else torch.int32
+        oc.scatter(k_pool[layer].view(raw).numpy(), data_o.k_new[layer].view(raw).numpy(), p.q_slot)
+        oc.scatter(v_pool[layer].view(raw).numpy(), data_o.v_new[layer].view(raw).numpy(), p.q_slot)
+        outs[layer] = oc.window_attn(hp.f64(data_o.q[layer]), hp.f64(k_pool[layer]), hp.f64(v_pool[layer]),
+                                     p.cu_q, p.q_pos, p.layout.block_table, w.n_q_heads, data_o.softmax_scale)
+    return k_rows, k_pool, v_pool, outs
+
+
+STEP_WORKLOADS = [
+    synth.CFG0,
+    synth.small_variant(synth.CFG1, n_layers=2),
+    synth.small_variant(synth.CFG2, n_streams=3, n_layers=2),
+    synth.small_variant(synth.CFG4, n_streams=4, n_layers=2),
+]
+
+
+@pytest.mark.parametrize("wi", range(len(STEP_WORKLOADS)))
+def test_whole_step_against_oracle(cs, wi):
+    """score -> plan -> re-rotate -> refresh write -> attention on a workload-shaped step; the HIP
+    path and the oracle each run the whole chain from the same seeded inputs."""
+    w = STEP_WORKLOADS[wi]
+    say(f"whole step: {w.name} streams={w.n_streams} layers={w.n_layers}")
+    data_g = engine.assemble_step(w, engine.hip_scorer, device="cpu")
+    data_o = engine.assemble_step(w, hp.oracle_scorer, device="cpu")
+    # (a) the two assemblies agree bit for bit, hence so do the plans
+    for name in ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "cu_q", "kv_len"):
+        assert np.array_equal(getattr(data_g.plan, name), getattr(data_o.plan, name)), name
+    assert np.array_equal(data_g.acc_in, data_o.acc_in)
+    say(f"  sizes: {data_g.info}")
+    step = engine.DeviceStep(data_g)
+    step.run()
+    torch.cuda.synchronize()
+    # (a) on the step's own frames
+    keep_w, idx_w, off_w, acc_w = hp.oracle_scorer(data_o.mv, data_o.sad, data_o.frame_type, data_o.cu_frames,
+                                                   data_o.acc_in, w, w.tau_mv_sq, w.tau_sad)
+    assert np.array_equal(step.keep.cpu().numpy(), keep_w)
+    assert np.array_equal(step.kept_off.cpu().numpy(), off_w)
+    assert np.array_equal(step.kept_idx.cpu().numpy()[: idx_w.size], idx_w)
+    assert np.array_equal(step.acc.cpu().numpy() != 0, acc_w != 0)
+    layers = list(range(w.n_layers))
+    k_rows, k_pool_o, v_pool_o, outs = _oracle_step(data_o, layers)
+    dst = torch.from_numpy(data_o.plan.dst_slot.astype(np.int64))
+    got_rows = step.k_pool.cpu()[:, dst].permute(1, 0, 2, 3).contiguous()
+    say(f"  rerotate: {hp.check_rerotated(got_rows, k_rows, w.dtype)}")
+    # (c) executed rows are bit-equal to the new K/V; values of reused rows are bit-equal copies
+    qs = torch.from_numpy(data_o.plan.q_slot.astype(np.int64))
+    assert torch.equal(step.k_pool.cpu()[:, qs], data_o.k_new) and torch.equal(step.v_pool.cpu()[:, qs], data_o.v_new)
+    assert torch.equal(step.v_pool.cpu(), v_pool_o)
+    for layer in layers:
+        say(f"  attention layer {layer}: {hp.check_attention(step.out[layer].cpu(), outs[layer], w.dtype)}")
+
+
+FULL_WORKLOADS = [synth.CFG1, synth.CFG2, synth.CFG3P, synth.CFG3D, synth.CFG4]
+
+
+@pytest.mark.parametrize("wi", range(len(FULL_WORKLOADS)))
+def test_full_size_step_sampled(cs, wi):
+    """The benchmark's own launch configuration at full size; the oracle checks (a) completely and
+    (b), (c), (d) on sampled rows / queries.  Big tensors are drawn on the GPU by torch's generator
+    and the sampled rows are copied to the host for the oracle."""
+    w = FULL_WORKLOADS[wi]
+    say(f"full-size step: {w.name}")
+    data = engine.assemble_step(w, engine.hip_scorer, device=DEV)
+    data_o = engine.assemble_step(w, hp.oracle_scorer, device="cpu", with_tensors=False)
+    for name in ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "cu_q", "kv_len"):
+        assert np.array_equal(getattr(data.plan, name), getattr(data_o.plan, name)), name
+    say(f"  sizes: {data.info}")
+    p = data.plan
+    rng = np.random.default_rng(900 + wi)
+    k_before = data.k_pool.clone()
+    v_before = data.v_pool.clone()
+    step = engine.DeviceStep(data)
+    step.run()
+    torch.cuda.synchronize()
+    keep_w, idx_w, off_w, _ = hp.oracle_scorer(data.mv, data.sad, data.frame_type, data.cu_frames, data.acc_in,
+                                               w, w.tau_mv_sq, w.tau_sad)
+    assert np.array_equal(step.keep.cpu().numpy(), keep_w)
+    assert np.array_equal(step.kept_off.cpu().numpy(), off_w)
+    assert np.array_equal(step.kept_idx.cpu().numpy()[: idx_w.size], idx_w)
+    # (b) sampled reused rows, all layers
+    n_rows = int(p.src_slot.size)
+    pick = np.sort(rng.choice(n_rows, size=min(256, n_rows), replace=False))
+    src = torch.from_numpy(p.src_slot[pick].astype(np.int64)).to(DEV)
+    dst = torch.from_numpy(p.dst_slot[pick].astype(np.int64)).to(DEV)
+    k_src = k_before[:, src].cpu()
+    k_ref = np.transpose(oc.rotate(hp.f64(k_src), p.delta[pick].astype(np.float64)[None, :, None], w.rope_base),
+                         (1, 0, 2, 3))
+    got = step.k_pool[:, dst].cpu().permute(1, 0, 2, 3).contiguous()
+    say(f"  rerotate ({pick.size} rows x {w.n_layers} layers): {hp.check_rerotated(got, k_ref, w.dtype)}")
+    assert torch.equal(step.v_pool[:, dst], v_before[:, src])
+    # (c) complete, bit exact (plain indexing is the definition)
+    qs = torch.from_numpy(p.q_slot.astype(np.int64)).to(DEV)
+    assert torch.equal(step.k_pool[:, qs], step.k_new) and torch.equal(step.v_pool[:, qs], step.v_new)
+    # rows that are neither a destination nor a refresh target are untouched
+    touched = torch.zeros(data.n_slots, dtype=torch.bool, device=DEV)
+    touched[qs] = True
+    touched[torch.from_numpy(p.dst_slot.astype(np.int64)).to(DEV)] = True
+    assert torch.equal(step.k_pool[:, ~touched], k_before[:, ~touched])
+    # (d) sampled queries of two layers, every head; the oracle reads the cache the GPU attention read
+    n_q = int(p.q_pos.size)
+    rows = np.sort(rng.choice(n_q, size=min(40, n_q), replace=False))
+    for layer in (0, w.n_layers - 1):
+        # cache for the oracle: reused rows re-rotated by the ORACLE (rounded), refresh rows from k_new
+        s_of = np.searchsorted(p.cu_q, rows, side="right") - 1
+        ref = np.zeros((rows.size, w.n_q_heads, w.head_dim))
+        for s in np.unique(s_of):
+            sel = rows[s_of == s]
+            n_ctx = int(p.q_pos[sel].max()) + 1
+            j = np.arange(n_ctx)
+            slots = p.layout.block_table[s, j // 16].astype(np.int64) * 16 + j % 16
+            kk = _oracle_cache_rows(k_before[layer], step.k_new[layer], p, slots, w, rotate=True)
+            vv = _oracle_cache_rows(v_before[layer], step.v_new[layer], p, slots, w, rotate=False)
+            bt_local = np.arange(-(-n_ctx // 16), dtype=np.int32)[None]
+            pad = bt_local.size * 16 - n_ctx
+            kk = np.concatenate([kk, np.zeros((pad,) + kk.shape[1:])])
+            vv = np.concatenate([vv, np.zeros((pad,) + vv.shape[1:])])
+            q_sel = hp.f64(step.q[layer][torch.from_numpy(sel.astype(np.int64)).to(DEV)])
+            ref[s_of == s] = oc.window_attn(q_sel, kk, vv, np.array([0, sel.size], np.int32), p.q_pos[sel],
+                                            bt_local, w.n_q_heads, data.softmax_scale)
+        got = step.out[layer][torch.from_numpy(rows.astype(np.int64)).to(DEV)].cpu()
+        say(f"  attention layer {layer} ({rows.size} queries): {hp.check_attention(got, ref, w.dtype)}")
+
+
+def _oracle_cache_rows(pool_before, new_rows, plan, slots, w, rotate):
+    """What the oracle says the new window's cache holds at `slots` (float64 [n, Hkv, d])."""
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    n_slots = pool_before.shape[0]
+    src_of = np.full(n_slots, -1, np.int64)
+    src_of[plan.dst_slot] = np.arange(plan.dst_slot.size)
+    new_of = np.full(n_slots, -1, np.int64)
+    new_of[plan.q_slot] = np.arange(plan.q_slot.size)
+    out = np.zeros((slots.size, w.n_kv_heads, w.head_dim))
+    is_new = new_of[slots] >= 0
+    out[is_new] = hp.f64(new_rows[torch.from_numpy(new_of[slots][is_new]).to(new_rows.device)])
+    reuse = ~is_new
+    assert np.all(src_of[slots][reuse] >= 0)
+    r = src_of[slots][reuse]
+    old = hp.f64(pool_before[torch.from_numpy(plan.src_slot[r].astype(np.int64)).to(pool_before.device)])
+    if rotate:
+        old = oc.rotate(old, plan.delta[r].astype(np.float64)[:, None], w.rope_base)
+        old = hp.f64(hp.round_like(old, tdt))
+    out[reuse] = old
+    return out
