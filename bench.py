@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the codec-guided window-prefill step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic streams:
+  cs_score_compact -> cs_kv_rerotate (all layers) -> per layer: cs_kv_refresh_scatter,
+  cs_window_prefill_attn.
+Inputs are resident in HBM before the timed region starts.  The step is captured once in a HIP
+graph and the timed region replays it K times (the refresh plan is built beforehand from an
+identical, untimed run of the scoring kernel; planning on the host is not part of the timed step).
+
+Printed: ONE JSON line with the whole-job throughput (executed tokens per second), a `roofline`
+object for the dominant kernel (event-timed on the launch stream) and a `cpu_baseline` object (the
+CPU oracle timed on this machine's host cores on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16
+DEFAULT_WORKLOAD = "cfg1_qwen7b_1stream"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD,
+                    help="one of the synthetic workloads in paper_2604_06036_amd.synth.WORKLOADS")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a HIP graph")
+    return ap.parse_args()
+
+
+def kernel_bytes_flops(w, info, n_layers):
+    """Algorithmic work per launch of each kernel (what the method itself must move / compute)."""
+    e = 2 if w.dtype == "bf16" else 4
+    row = w.n_kv_heads * w.head_dim * e
+    n_frames = w.n_streams * w.stride
+    patches = n_frames * w.patches
+    tokens = n_frames * w.tokens_per_frame
+    a_bytes = patches * (4 + (4 if w.use_residual else 0) + 2) + tokens * 1 + info["kept_new"] * 4 + (n_frames + 1) * 4
+    b_bytes = info["n_reuse"] * (n_layers * 4 * row + 12)          # K read+write, V read+write, 3 index words
+    c_bytes = info["n_q"] * (4 * row + 4)                           # K,V new read + K,V cache write + slot
+    d_flops = 4.0 * w.head_dim * w.n_q_heads * info["visible_pairs"]
+    d_bytes = 2 * info["kv_len_total"] * row + 2 * info["n_q"] * w.n_q_heads * w.head_dim * e
+    return dict(a_bytes=a_bytes, b_bytes=b_bytes, c_bytes=c_bytes, d_flops=d_flops, d_bytes=d_bytes)
+
+
+def event_time(torch, fn, reps):
+    """Average milliseconds of fn(), bracketed by HIP events on the current (launch) stream."""
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def cpu_baseline(w, data, step, torch):
+    """The oracle, as it stands, on the host: scoring, re-rotation of every reused row for all
+    layers, then refresh write + attention for a bounded number of layers, scaled to all layers."""
+    import numpy as np
+    from oracle import codecsight_oracle as oc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    p = data.plan
+    f64 = lambda t: t.detach().cpu().float().numpy().astype(np.float64)
+    pairs_per_layer = w.n_q_heads * data.info["visible_pairs"]
+    # keep the sample near 10-30 s: the fp64 oracle sustains very roughly 2e9 pair-dims/s per core
+    budget_pairs = 1.0e9 * max(1, cores)
+    n_l = int(max(1, min(w.n_layers, budget_pairs // max(1.0, pairs_per_layer * w.head_dim / 64))))
+    max_rows = 4096
+    rows = p.src_slot.shape[0]
+    pick = np.arange(rows) if rows <= max_rows else np.sort(np.random.default_rng(0).choice(rows, max_rows, replace=False))
+    k_host = step.k_pool_before[:, torch.from_numpy(p.src_slot[pick].astype(np.int64)).to(step.dev)].cpu()
+    t0 = time.perf_counter()
+    oc.score_compact(data.mv, data.sad if w.use_residual else None, None, data.frame_type, data.cu_frames,
+                     data.acc_in, w.grid_h, w.grid_w, w.group, w.tau_mv_sq, w.tau_sad, w.use_residual)
+    t_a = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oc.rotate(f64(k_host), p.delta[pick].astype(np.float64)[None, :, None], w.rope_base)
+    t_b = (time.perf_counter() - t0) * rows / max(1, pick.size)
+    # layers: cache after (b) is taken as given (copying device results to the host is not timed)
+    q_sel = None
+    n_q = int(p.q_pos.size)
+    max_q = 2048
+    qrows = None if n_q <= max_q else np.sort(np.random.default_rng(1).choice(n_q, max_q, replace=False))
+    t_cd = 0.0
+    for layer in range(n_l):
+        k_l, v_l = f64(step.k_pool[layer]), f64(step.v_pool[layer])
+        kn, vn, q_l = f64(step.k_new[layer]), f64(step.v_new[layer]), f64(step.q[layer])
+        t0 = time.perf_counter()
+        oc.scatter(k_l, kn, p.q_slot)
+        oc.scatter(v_l, vn, p.q_slot)
+        t_c = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oc.window_attn(q_l, k_l, v_l, p.cu_q, p.q_pos, p.layout.block_table, w.n_q_heads,
+                       data.softmax_scale, rows=qrows)
+        t_d = (time.perf_counter() - t0) * (1.0 if qrows is None else n_q / qrows.size)
+        t_cd += t_c + t_d
+    t_step = t_a + t_b + w.n_layers * t_cd / n_l
+    sample = (f"oracle: scoring of the step's frames; re-rotation of {pick.size} of {rows} reused rows x "
+              f"{w.n_layers} layers (scaled to all rows); refresh write + attention of {n_l} of {w.n_layers} "
+              f"layers" + ("" if qrows is None else f" on {qrows.size} of {n_q} queries") + " (scaled to the full step)")
+    return dict(value=n_q / t_step, unit="tokens/s", cores=int(cores), kind="oracle", sample=sample,
+                seconds_per_step=t_step)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards by stream with no exchange step; "
+              "no multi-GPU figure is produced). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2604_06036_amd import binding, engine, synth
+
+    if not os.path.exists(binding.LIB_PATH):
+        print("bench.py: libcodecsight.so is missing; run `python -m paper_2604_06036_amd.build` "
+              "(there is no CPU fallback)", file=sys.stderr)
+        sys.exit(3)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    t_setup = time.perf_counter()
+    data = engine.assemble_step(w, engine.hip_scorer, device="cuda")
+    step = engine.DeviceStep(data)
+    step.k_pool_before = step.k_pool.clone()     # pre-step cache, for the CPU baseline's re-rotation leg
+    info = data.info
+    work = kernel_bytes_flops(w, info, w.n_layers)
+    print(f"[bench] {w.name}: {info} setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
+
+    # ---- the timed region: W warm-up steps, then exactly K steps
+    launch = "eager"
+    run_step = step.run
+    graph = None
+    if not args.eager:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step.run()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step.run()
+            run_step = graph.replay
+            launch = "hipgraph"
+        except Exception as exc:  # capture unsupported: fall back to eager launches, and say so
+            print(f"[bench] graph capture failed ({exc}); using eager launches", file=sys.stderr)
+            run_step, launch = step.run, "eager"
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = info["n_q"] / (ms_per_step * 1e-3)
+
+    # ---- per-kernel clocks: HIP events on the launch stream around back-to-back launches
+    L = w.n_layers
+    reps = max(3, min(args.steps, 20))
+    t_a = event_time(torch, step.score_compact, reps)
+    t_b = event_time(torch, step.rerotate, reps)
+    t_c = event_time(torch, lambda: [step.refresh_scatter(l) for l in range(L)], reps) / L
+    t_d = event_time(torch, lambda: [step.attention(l) for l in range(L)], reps) / L
+    kernels = {
+        "cs_score_compact": dict(ms=t_a, launches_per_step=1, GBps=work["a_bytes"] / t_a / 1e6),
+        "cs_kv_rerotate": dict(ms=t_b, launches_per_step=1, GBps=work["b_bytes"] / t_b / 1e6),
+        "cs_kv_refresh_scatter": dict(ms=t_c, launches_per_step=L, GBps=work["c_bytes"] / t_c / 1e6),
+        "cs_window_prefill_attn": dict(ms=t_d, launches_per_step=L, TFLOPs=work["d_flops"] / t_d / 1e9,
+                                       GBps=work["d_bytes"] / t_d / 1e6),
+    }
+    share = {k: v["ms"] * v["launches_per_step"] for k, v in kernels.items()}
+    dominant = max(share, key=share.get)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(w.name, {}).get(dominant)
+        except Exception:
+            traffic = None
+    if dominant == "cs_window_prefill_attn":
+        ach = kernels[dominant]["TFLOPs"]
+        roofline = dict(bound="mfma", kernel="window_attn_bf16_kernel" if w.dtype == "bf16" else "window_attn_f32_kernel",
+                        achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS,
+                        traffic=traffic, flops_per_launch=work["d_flops"], ms_per_launch=t_d)
+    else:
+        ach = kernels[dominant]["GBps"]
+        key = {"cs_score_compact": "a_bytes", "cs_kv_rerotate": "b_bytes", "cs_kv_refresh_scatter": "c_bytes"}[dominant]
+        roofline = dict(bound="hbm", kernel=dominant, achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=ach / PEAK_HBM_GBS, traffic=traffic, bytes_per_launch=work[key],
+                        ms_per_launch=kernels[dominant]["ms"])
+
+    out = {
+        "metric": "window-prefill tokens/s per MI355X (executed refresh+new+text tokens per second, whole step)",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "streams": w.n_streams, "layers": w.n_layers,
+                   "heads": f"{w.n_q_heads}/{w.n_kv_heads}", "head_dim": w.head_dim,
+                   "window_frames": w.window, "stride_frames": w.stride, "tokens_per_frame": w.tokens_per_frame,
+                   "executed_tokens": info["n_q"], "reused_rows": info["n_reuse"],
+                   "window_tokens": info["kv_len_total"], "launch": launch},
+        "window_tokens_per_s": info["kv_len_total"] / (ms_per_step * 1e-3),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, data, step, torch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
