@@ -181,7 +181,8 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  *  workspace     cs_window_prefill_attn_workspace() bytes (may be 0, then NULL is accepted)
  * Errors: CS_EINVAL (null pointer, negative size, n_q_heads not a multiple of n_kv_heads),
  *         CS_EUNSUPPORTED (head_dim not in {64,128}, block_size != 16, n_q_heads/n_kv_heads > 16,
- *         strides not multiples of 16 bytes, unknown dtype), CS_EWORKSPACE, CS_EHIP.
+ *         strides not multiples of 16 bytes, unknown dtype, max_blocks > 8192 for CS_BF16),
+ *         CS_EWORKSPACE, CS_EHIP.
  *         n_q == 0 or n_streams == 0 returns CS_OK.
  * ------------------------------------------------------------------------------------------ */
 size_t cs_window_prefill_attn_workspace(int64_t n_q, int32_t n_streams, int32_t n_q_heads,

@@ -50,9 +50,15 @@ struct AttnParams {
 constexpr int kBM = 128;   // rows per workgroup (4 waves x 32)
 constexpr int kBN = 64;    // keys per LDS tile
 constexpr float kNegInf = -INFINITY;
+constexpr int kMaxBlocksInLds = 8192;   // block-table row staged in LDS: windows up to 131072 tokens
 
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// Two fp32 -> packed bf16 (round to nearest even) in one v_cvt_pk_bf16_f32.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return static_cast<uint32_t>(cs::f32_to_bf16(lo)) | (static_cast<uint32_t>(cs::f32_to_bf16(hi)) << 16);
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 template <int D>
@@ -67,6 +73,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
 
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBN * KP];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBN * VP];
+  extern __shared__ int32_t s_bt[];    // this stream's block-table row (max_blocks entries)
 
   // ---- which (stream, row tile) is this workgroup?  longest tiles of a stream come first
   int x = blockIdx.x, s = 0, q0 = 0, rows_total = 0, n_row_tiles = 0;
@@ -123,6 +130,11 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
   const uint16_t* vbase = static_cast<const uint16_t*>(p.v) + kvh * p.stride_head + st_chunk * 8;
   cs::u32x4 kreg[PASSES], vreg[PASSES];
 
+  // the block-table entries this workgroup can touch, staged once so that a tile fetch is one
+  // LDS lookup followed by independent global loads (no dependent global round trip per tile)
+  for (int i = tid; i <= wg_max / CS_KV_BLOCK; i += 256) s_bt[i] = bt[i];
+  __syncthreads();
+
   auto fetch = [&](int key_tile) {
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
@@ -130,7 +142,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
       kreg[i] = cs::u32x4{0, 0, 0, 0};
       vreg[i] = cs::u32x4{0, 0, 0, 0};
       if (j <= wg_max) {
-        const int64_t slot = static_cast<int64_t>(bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
+        const int64_t slot = static_cast<int64_t>(s_bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
         kreg[i] = *reinterpret_cast<const cs::u32x4*>(kbase + slot * p.stride_slot);
         vreg[i] = *reinterpret_cast<const cs::u32x4*>(vbase + slot * p.stride_slot);
       }
@@ -384,10 +396,12 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
     const int64_t tiles = (n_q * group) / kBM + n_streams;
     if (tiles > 0x7fffffffll) return CS_EUNSUPPORTED;
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_kv_heads));
+    if (max_blocks > kMaxBlocksInLds) return CS_EUNSUPPORTED;
+    const size_t bt_bytes = static_cast<size_t>(max_blocks) * sizeof(int32_t);
     if (head_dim == 128)
-      hipLaunchKernelGGL(window_attn_bf16_kernel<128>, grid, dim3(256), 0, st, p);
+      hipLaunchKernelGGL(window_attn_bf16_kernel<128>, grid, dim3(256), bt_bytes, st, p);
     else
-      hipLaunchKernelGGL(window_attn_bf16_kernel<64>, grid, dim3(256), 0, st, p);
+      hipLaunchKernelGGL(window_attn_bf16_kernel<64>, grid, dim3(256), bt_bytes, st, p);
   } else {
     const int64_t units = n_q * n_q_heads;
     const dim3 grid(static_cast<unsigned>((units + 3) / 4));
