@@ -61,6 +61,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// Running-max slack of the online softmax, in log2 units: the reference maximum of a row is only
+// raised (and the accumulators rescaled) when the tile maximum exceeds it by more than this, so
+// probabilities stay below 2^kMaxSlack and almost every tile skips the rescale.
+constexpr float kMaxSlack = 8.0f;
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) {
   constexpr int KP = D + 8;            // K tile pitch (elements): rows shift by 4 banks
@@ -69,7 +74,9 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
   constexpr int DB = D / 32;           // 32-wide blocks of the head dimension in O^T
   constexpr int CPR = D / 8;           // 16-byte chunks per cache row
   constexpr int RPP = 256 / CPR;       // rows staged per pass by the whole workgroup
+  constexpr int RPW = 64 / CPR;        // rows staged per pass by one wave (inside one cache block)
   constexpr int PASSES = kBN / RPP;
+  constexpr int BPT = kBN / CS_KV_BLOCK;   // cache blocks per key tile
 
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBN * KP];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBN * VP];
@@ -88,7 +95,8 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
   const int r_tile = (n_row_tiles - 1 - x) * kBM;
   const int kvh = blockIdx.y;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
 
   // ---- this lane's row (query token, head) and causal frontier
@@ -107,6 +115,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
   const int wave_min = wave_live ? p.q_pos[q0 + w_first / p.group] : -1;
   const int wave_max = wave_live ? p.q_pos[q0 + w_last / p.group] : -1;
   const int n_key_tiles = wg_max / kBN + 1;
+  const int last_blk = wg_max / CS_KV_BLOCK;
 
   // ---- Q^T fragments: lane = (query n, half h) holds d-slice [16*step + 8h, +8)
   const uint16_t* qrow = static_cast<const uint16_t*>(p.q) +
@@ -122,34 +131,45 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = kNegInf, l_run = 0.f;
+  const float slack = kMaxSlack / p.scale_log2e;          // in raw score units
 
-  // ---- staging of K/V tiles: thread -> (row tid / CPR + pass * RPP, chunk tid % CPR)
+  // ---- staging of K/V tiles.  Thread -> row st_row + pass * RPP of the tile, chunk st_chunk.
+  // A wave's rows of one pass lie inside one 16-token cache block, so the block id is
+  // wave-uniform and the per-lane part of the address never changes.
   const int st_row = tid / CPR, st_chunk = tid % CPR;
   const int32_t* bt = p.block_table + static_cast<int64_t>(s) * p.max_blocks;
-  const uint16_t* kbase = static_cast<const uint16_t*>(p.k) + kvh * p.stride_head + st_chunk * 8;
-  const uint16_t* vbase = static_cast<const uint16_t*>(p.v) + kvh * p.stride_head + st_chunk * 8;
+  const int64_t lane_off = static_cast<int64_t>(st_row % CS_KV_BLOCK) * p.stride_slot +
+                           static_cast<int64_t>(kvh) * p.stride_head + st_chunk * 8;
+  const uint16_t* kbase = static_cast<const uint16_t*>(p.k) + lane_off;
+  const uint16_t* vbase = static_cast<const uint16_t*>(p.v) + lane_off;
+  const int64_t blk_stride = static_cast<int64_t>(CS_KV_BLOCK) * p.stride_slot;
   cs::u32x4 kreg[PASSES], vreg[PASSES];
 
-  // the block-table entries this workgroup can touch, staged once so that a tile fetch is one
-  // LDS lookup followed by independent global loads (no dependent global round trip per tile)
-  for (int i = tid; i <= wg_max / CS_KV_BLOCK; i += 256) s_bt[i] = bt[i];
+  for (int i = tid; i <= last_blk; i += 256) s_bt[i] = bt[i];
   __syncthreads();
 
-  auto fetch = [&](int key_tile) {
+  // Full tiles: every row is a live cache entry.  The last tile may end inside a block (rows past
+  // the frontier are staged as zeros: they can hold anything) or before a block the table does
+  // not define (never read).
+  auto fetch = [&](int key_tile, bool last) {
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
-      const int j = key_tile * kBN + st_row + i * RPP;
+      const int bi = key_tile * BPT + (i * RPP + wave * RPW) / CS_KV_BLOCK;     // wave-uniform
       kreg[i] = cs::u32x4{0, 0, 0, 0};
       vreg[i] = cs::u32x4{0, 0, 0, 0};
-      if (j <= wg_max) {
-        const int64_t slot = static_cast<int64_t>(s_bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
-        kreg[i] = *reinterpret_cast<const cs::u32x4*>(kbase + slot * p.stride_slot);
-        vreg[i] = *reinterpret_cast<const cs::u32x4*>(vbase + slot * p.stride_slot);
+      if (!last || bi <= last_blk) {
+        const int64_t blk = __builtin_amdgcn_readfirstlane(s_bt[bi]);
+        kreg[i] = *reinterpret_cast<const cs::u32x4*>(kbase + blk * blk_stride);
+        vreg[i] = *reinterpret_cast<const cs::u32x4*>(vbase + blk * blk_stride);
+        if (last && key_tile * kBN + st_row + i * RPP > wg_max) {
+          kreg[i] = cs::u32x4{0, 0, 0, 0};
+          vreg[i] = cs::u32x4{0, 0, 0, 0};
+        }
       }
     }
   };
 
-  fetch(0);
+  if (n_key_tiles == 1) fetch(0, true); else fetch(0, false);
   for (int kt = 0; kt < n_key_tiles; ++kt) {
     __syncthreads();                       // everyone is done reading the previous tile
 #pragma unroll
@@ -159,19 +179,23 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
       *reinterpret_cast<cs::u32x4*>(&sV[r * VP + st_chunk * 8]) = vreg[i];
     }
     __syncthreads();
-    if (kt + 1 < n_key_tiles) fetch(kt + 1);
+    if (kt + 2 < n_key_tiles) fetch(kt + 1, false);
+    else if (kt + 1 < n_key_tiles) fetch(kt + 1, true);
 
     const int j0 = kt * kBN;
     if (j0 > wave_max) continue;           // wholly above this wave's frontier (wave-uniform)
 
-    // ---- S^T = K Q^T for the 64 keys of the tile: two 32-key blocks
+    // ---- S^T = K Q^T for the 64 keys of the tile: two 32-key blocks, MFMAs alternate between
+    //      the two accumulators so that consecutive ones are independent
     f32x16 sacc[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
 #pragma unroll
-      for (int st = 0; st < STEPS; ++st) {
+    for (int st = 0; st < STEPS; ++st) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
         const bf16x8 a = __builtin_bit_cast(
             bf16x8, *reinterpret_cast<const cs::u32x4*>(&sK[(kb * 32 + n) * KP + 16 * st + 8 * h]));
         sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], sacc[kb], 0, 0, 0);
@@ -193,53 +217,53 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
 #pragma unroll
       for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[kb][r]);
     t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
-    const float m_new = fmaxf(m_run, t_max);
-    const float m_use = m_new == kNegInf ? 0.f : m_new;      // rows with nothing visible yet
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * p.scale_log2e);
-    const float m_scaled = m_use * p.scale_log2e;
-    float t_sum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], p.scale_log2e, -m_scaled));
-        sacc[kb][r] = e;
-        t_sum += e;
-      }
-    l_run = fmaf(l_run, alpha, t_sum);
-    m_run = m_new;
-    if (__any(alpha != 1.f)) {
+    // raise the row's reference maximum only when the tile exceeds it by more than the slack
+    // (always on the first visible key: m_run = -inf); both half-waves take the same decision
+    if (__any(t_max > m_run + slack)) {
+      const bool up = t_max > m_run + slack;
+      const float m_new = up ? t_max : m_run;
+      const float alpha = up ? __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e) : 1.f;
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
     }
+    const float m_scaled = (m_run == kNegInf ? 0.f : m_run) * p.scale_log2e;
 
-    // ---- O^T += V^T P^T.  MFMA (kb, mm) contracts S registers 8mm..8mm+7 of block kb; slot
-    //      8h + i of the contraction is key 32 kb + 16 mm + 8 (i / 4) + 4 h + i % 4.
+    // ---- P = exp2(S c - m c), packed to bf16 in B-operand order.  MFMA (kb, mm) contracts S
+    //      registers 8mm..8mm+7 of block kb; slot 8h + i of the contraction is key
+    //      32 kb + 16 mm + 8 (i / 4) + 4 h + i % 4.  Row sums are taken over the rounded values.
     bf16x8 pb[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
         cs::u32x4 w;
-        w.x = pack_bf16x2(sacc[kb][8 * mm + 0], sacc[kb][8 * mm + 1]);
-        w.y = pack_bf16x2(sacc[kb][8 * mm + 2], sacc[kb][8 * mm + 3]);
-        w.z = pack_bf16x2(sacc[kb][8 * mm + 4], sacc[kb][8 * mm + 5]);
-        w.w = pack_bf16x2(sacc[kb][8 * mm + 6], sacc[kb][8 * mm + 7]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
+          const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
+          const uint32_t pk = pack_bf16x2(e0, e1);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
+                                                  __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run, false);
+          w[c] = pk;
+        }
         pb[kb][mm] = __builtin_bit_cast(bf16x8, w);
       }
-    // transpose read: lane i of a 16-lane group supplies &V[key0 + i / 4][col0 + 4 (i % 4)] and
-    // receives V[key0 + 0..3][col0 + i]
+
+    // ---- O^T += V^T P^T.  Transpose read: lane i of a 16-lane group supplies
+    //      &V[key0 + i / 4][col0 + 4 (i % 4)] and receives V[key0 + 0..3][col0 + i]
     const int i16 = lane & 15, gid = (lane >> 4) & 1;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const int col = 32 * db + 16 * gid + 4 * (i16 & 3);
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int mm = 0; mm < 2; ++mm) {
+        const int key0 = 32 * kb + 16 * mm + 4 * h + (i16 >> 2);
 #pragma unroll
-        for (int mm = 0; mm < 2; ++mm) {
-          const int key0 = 32 * kb + 16 * mm + 4 * h + (i16 >> 2);
+        for (int db = 0; db < DB; ++db) {
+          const int col = 32 * db + 16 * gid + 4 * (i16 & 3);
           const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
               (lds_s16x4*)(&sV[key0 * VP + col]));
           const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -248,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kb][mm],
                                                          o[db], 0, 0, 0);
         }
-    }
+      }
   }
 
   // ---- normalise and store: register r of block db is d = 32 db + 8 (r / 4) + 4 h + r % 4
