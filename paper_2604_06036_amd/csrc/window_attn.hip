@@ -155,16 +155,14 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
       const int bi = key_tile * BPT + (i * RPP + wave * RPW) / CS_KV_BLOCK;     // wave-uniform
-      kreg[i] = cs::u32x4{0, 0, 0, 0};
-      vreg[i] = cs::u32x4{0, 0, 0, 0};
       if (!last || bi <= last_blk) {
         const int64_t blk = __builtin_amdgcn_readfirstlane(s_bt[bi]);
         kreg[i] = *reinterpret_cast<const cs::u32x4*>(kbase + blk * blk_stride);
         vreg[i] = *reinterpret_cast<const cs::u32x4*>(vbase + blk * blk_stride);
-        if (last && key_tile * kBN + st_row + i * RPP > wg_max) {
-          kreg[i] = cs::u32x4{0, 0, 0, 0};
-          vreg[i] = cs::u32x4{0, 0, 0, 0};
-        }
+      }
+      if (last && (bi > last_blk || key_tile * kBN + st_row + i * RPP > wg_max)) {
+        kreg[i] = cs::u32x4{0, 0, 0, 0};
+        vreg[i] = cs::u32x4{0, 0, 0, 0};
       }
     }
   };
@@ -188,17 +186,14 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
     // ---- S^T = K Q^T for the 64 keys of the tile: two 32-key blocks, MFMAs alternate between
     //      the two accumulators so that consecutive ones are independent
     f32x16 sacc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int st = 0; st < STEPS; ++st) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         const bf16x8 a = __builtin_bit_cast(
             bf16x8, *reinterpret_cast<const cs::u32x4*>(&sK[(kb * 32 + n) * KP + 16 * st + 8 * h]));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], sacc[kb], 0, 0, 0);
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], st == 0 ? zero16 : sacc[kb], 0, 0, 0);
       }
     }
     // register r of block kb is key j0 + 32 kb + 8 (r / 4) + 4 h + r % 4 of query n
