@@ -176,9 +176,13 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  *
  *  q, out        [n_q][n_q_heads][head_dim] contiguous, 16-byte aligned
  *  cu_q          int32 [n_streams+1], cu_q[0] = 0, cu_q[n_streams] = n_q
- *  q_pos         int32 [n_q];  kv_len int32 [n_streams] (only an upper bound for q_pos)
+ *  q_pos         int32 [n_q];  kv_len int32 [n_streams]: q_pos < kv_len, and block_table row s
+ *                defines entries 0 .. ceil(kv_len[s]/16)-1
  *  block_table   int32 [n_streams][max_blocks]
- *  workspace     cs_window_prefill_attn_workspace() bytes (may be 0, then NULL is accepted)
+ *  workspace     cs_window_prefill_attn_workspace() bytes for the same shape arguments, 16-byte
+ *                aligned (may be 0, then NULL is accepted).  Holds the partial results of row
+ *                tiles whose key sweep is shared by several workgroups; contents need not be
+ *                initialised.  Two calls that overlap in time must not share a workspace.
  * Errors: CS_EINVAL (null pointer, negative size, n_q_heads not a multiple of n_kv_heads),
  *         CS_EUNSUPPORTED (head_dim not in {64,128}, block_size != 16, n_q_heads/n_kv_heads > 16,
  *         strides not multiples of 16 bytes, unknown dtype, max_blocks > 8192 for CS_BF16),
@@ -186,7 +190,8 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  *         n_q == 0 or n_streams == 0 returns CS_OK.
  * ------------------------------------------------------------------------------------------ */
 size_t cs_window_prefill_attn_workspace(int64_t n_q, int32_t n_streams, int32_t n_q_heads,
-                                        int32_t n_kv_heads, int32_t head_dim, int32_t dtype);
+                                        int32_t n_kv_heads, int32_t head_dim, int32_t max_blocks,
+                                        int32_t dtype);
 
 int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void* v_cache_layer,
                            const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,

@@ -66,7 +66,7 @@ def lib() -> ctypes.CDLL:
     L.cs_kv_refresh_scatter.restype = c.c_int
     L.cs_kv_refresh_scatter.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i64, i64, i32, vp]
     L.cs_window_prefill_attn_workspace.restype = sz
-    L.cs_window_prefill_attn_workspace.argtypes = [i64, i32, i32, i32, i32, i32]
+    L.cs_window_prefill_attn_workspace.argtypes = [i64, i32, i32, i32, i32, i32, i32]
     L.cs_window_prefill_attn.restype = c.c_int
     L.cs_window_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, i64, i32, i32, i32,
                                          i32, i64, i64, f32, i32, vp, sz, vp]
@@ -154,9 +154,9 @@ def cs_kv_refresh_scatter(k_new, v_new, slot, k_cache_layer, v_cache_layer, n_to
         n_kv_heads, head_dim, stride_slot, stride_head, dtype, _stream()))
 
 
-def cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, head_dim, dtype) -> int:
+def cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, head_dim, max_blocks, dtype) -> int:
     return int(lib().cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, head_dim,
-                                                      dtype))
+                                                      max_blocks, dtype))
 
 
 def cs_window_prefill_attn(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks,

@@ -41,10 +41,20 @@ struct AttnParams {
   const int32_t* __restrict__ cu_q;
   const int32_t* __restrict__ q_pos;
   const int32_t* __restrict__ block_table;
+  const int32_t* __restrict__ kv_len;
   int64_t stride_slot, stride_head;
   int32_t max_blocks, n_streams, n_q_heads, n_kv_heads, group;
   float scale, scale_log2e;
   int64_t n_q;
+  int32_t xcd_chunk;     // > 0: workgroup b runs item (b % 8) * xcd_chunk + b / 8
+  // split-KV (max_splits > 1): a row tile whose key sweep is longer than chunk_tiles key tiles is
+  // shared by several workgroups; their un-normalised partial results go to the workspace and a
+  // second kernel merges them (merging in the last workgroup to finish was tried and is far
+  // slower here: the device-scope release/acquire it needs writes back and invalidates the L2)
+  int32_t chunk_tiles, max_splits, bm;
+  int32_t* ws_desc;      // [items][8]: q0, rows_total, r_tile, kvh, n_split
+  float* ws_ml;          // [items][max_splits][bm][2]: running max (raw score units), row sum
+  float* ws_o;           // [items][max_splits][bm][128]: un-normalised output rows
 };
 
 constexpr int kBM = 128;   // rows per workgroup (4 waves x 32)
@@ -289,6 +299,383 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
 }
 
 // ------------------------------------------------------------------------------------------
+// Asynchronous-pipeline variant for head_dim 128 (the shape of every bf16 workload measured).
+//
+// Same mathematics and register layouts as the kernel above; what changes is how K/V tiles reach
+// LDS.  Tiles are copied global -> LDS by the DMA form of the global load
+// (global_load_lds_dwordx4: lane l of a wave deposits its 16 bytes at base + 16 l, the source
+// address is free per lane), NS tiles deep, so nothing is staged through registers, there is one
+// workgroup barrier per tile instead of two, and a tile is requested NS-1 tiles before it is
+// used.  Because the DMA fixes the LDS position of each lane's chunk, bank conflicts are avoided
+// by choosing WHICH 16-byte chunk of a row each lane fetches (an XOR swizzle on the source side)
+// instead of padding rows:
+//   K tile row r: chunk c is stored at position c ^ (r % 16)       (ds_read_b128 of 16 rows at one c)
+//   V tile row r: chunk c is stored at position c ^ (2 (r % 8))    (transpose reads: 4 rows x 2 chunks)
+// NW = 8 waves (256 rows, one workgroup per CU, NS = 4) for large grids, NW = 4 (128 rows, two
+// workgroups per CU, NS = 2) otherwise.  Workgroups are numbered so that all row tiles of one
+// (stream, kv head) pair run on the same XCD (shared L2) when there are enough pairs to balance.
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// One 16-byte-per-lane DMA copy global -> LDS (lane l lands at lds_addr + 16 l).  Issued as inline
+// assembly on purpose: the compiler then keeps no scoreboard entry for it and does not drain the
+// whole prefetch queue before the next LDS read; completion is enforced by the explicit vmcnt
+// waits and workgroup barriers of the pipeline below.  The "memory" clobber tells the compiler
+// that LDS contents change here.
+__device__ __forceinline__ void dma16(const void* gsrc, const void* lds_dst) {
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)lds_dst));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gsrc), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
+  // 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8 left at their maxima)
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+template <int NW, int NS>
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_async_kernel(AttnParams p) {
+  constexpr int D = 128;
+  constexpr int BM = 32 * NW;           // rows per workgroup
+  constexpr int STEPS = D / 16, DB = D / 32;
+  constexpr int TILE = kBN * D;         // elements of one K (or V) tile: 16 KiB, unpadded
+  constexpr int IPW = 16 / NW;          // 1-KiB DMA instructions per wave, per tile, per tensor
+  constexpr int AHEAD = NS - 1;         // tiles requested ahead of the one being computed
+
+  __shared__ __attribute__((aligned(1024))) uint16_t sK[NS][TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t sV[NS][TILE];
+  extern __shared__ int32_t s_bt[];
+
+  // ---- work item: XCD-aware renumbering, then (stream, kv head, row tile).  Every wave finds
+  //      the stream by a 64-streams-at-a-time prefix sum over cu_q (a serial scan of cu_q costs
+  //      one dependent memory round trip per stream, microseconds for the last streams).
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  int v = blockIdx.x;
+  if (p.xcd_chunk > 0) v = (v & 7) * p.xcd_chunk + (v >> 3);
+  const int split = v % p.max_splits;
+  v /= p.max_splits;
+  const int item = v;
+  int s = -1, q0 = 0, rows_total = 0, n_row_tiles = 0;
+  for (int s0 = 0; s0 < p.n_streams; s0 += 64) {
+    const int si = s0 + lane;
+    int c0 = 0, c1 = 0;
+    if (si < p.n_streams) {
+      c0 = p.cu_q[si];
+      c1 = p.cu_q[si + 1];
+    }
+    const int rows_i = (c1 - c0) * p.group;
+    const int tiles_i = (rows_i + BM - 1) / BM;
+    const int items_i = tiles_i * p.n_kv_heads;
+    int incl = items_i;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(incl, off);
+      if (lane >= off) incl += t;
+    }
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    if (v < total) {
+      const int hit = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(__ballot(incl > v))) - 1);
+      s = s0 + hit;
+      q0 = __builtin_amdgcn_readlane(c0, hit);
+      rows_total = __builtin_amdgcn_readlane(rows_i, hit);
+      n_row_tiles = __builtin_amdgcn_readlane(tiles_i, hit);
+      v -= __builtin_amdgcn_readlane(incl, hit) - __builtin_amdgcn_readlane(items_i, hit);
+      break;
+    }
+    v -= total;
+  }
+  if (s < 0) {
+    if (p.max_splits > 1 && split == 0 && tid == 0) p.ws_desc[item * 8 + 4] = 0;   // nothing to merge
+    return;
+  }
+  const int kvh = v / n_row_tiles;
+  const int r_tile = (n_row_tiles - 1 - (v - kvh * n_row_tiles)) * BM;      // longest first
+
+  // the stream's block-table row goes to LDS; its length comes from kv_len so that these loads do
+  // not wait for the causal frontier (q_pos) to arrive
+  const int32_t* bt = p.block_table + static_cast<int64_t>(s) * p.max_blocks;
+  {
+    const int n_blk = min((p.kv_len[s] + CS_KV_BLOCK - 1) / CS_KV_BLOCK, p.max_blocks);
+    for (int i = tid; i < n_blk; i += NW * 64) s_bt[i] = bt[i];
+  }
+
+  const int row = r_tile + wave * 32 + n;
+  const bool valid = row < rows_total;
+  const int row_c = valid ? row : rows_total - 1;
+  const int tok = q0 + row_c / p.group;
+  const int head = kvh * p.group + row_c % p.group;
+  const int lim = valid ? p.q_pos[tok] : -1;
+
+  const int wg_last = min(r_tile + BM, rows_total) - 1;
+  const int wg_max = p.q_pos[q0 + wg_last / p.group];
+  const int w_first = r_tile + wave * 32;
+  const bool wave_live = w_first < rows_total;
+  const int w_last = min(w_first + 31, rows_total - 1);
+  const int wave_min = wave_live ? p.q_pos[q0 + w_first / p.group] : -1;
+  const int wave_max = wave_live ? p.q_pos[q0 + w_last / p.group] : -1;
+  const int n_key_tiles = wg_max / kBN + 1;
+  const int last_blk = wg_max / CS_KV_BLOCK;
+  const int n_split = (n_key_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
+  if (p.max_splits > 1 && split == 0 && tid == 0) {
+    int32_t* d = p.ws_desc + item * 8;
+    d[0] = q0; d[1] = rows_total; d[2] = r_tile; d[3] = kvh; d[4] = n_split;
+  }
+  if (split >= n_split) return;
+  const int kt_begin = split * p.chunk_tiles;
+  const int kt_end = min(n_key_tiles, kt_begin + p.chunk_tiles);
+
+  const uint16_t* qrow = static_cast<const uint16_t*>(p.q) +
+                         (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
+  bf16x8 qf[STEPS];
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st)
+    qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(qrow + 16 * st + 8 * h));
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = kNegInf, l_run = 0.f;
+  const float slack = kMaxSlack / p.scale_log2e;
+
+  // ---- DMA sources.  Instruction i of this wave moves tile rows 4 q .. 4 q + 3, q = wave*IPW + i;
+  //      lane l lands at (row 4 q + l / 16, position l % 16) and fetches the chunk that belongs there.
+  const uint16_t* kglob = static_cast<const uint16_t*>(p.k) + static_cast<int64_t>(kvh) * p.stride_head;
+  const uint16_t* vglob = static_cast<const uint16_t*>(p.v) + static_cast<int64_t>(kvh) * p.stride_head;
+  const int64_t blk_stride = static_cast<int64_t>(CS_KV_BLOCK) * p.stride_slot;
+  const int l_row = lane >> 4, l_pos = lane & 15;
+  int64_t k_off[IPW], v_off[IPW];      // element offsets inside a cache block, constant per lane
+  int k_chunk[IPW], v_chunk[IPW];
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int trow = 4 * (wave * IPW + i) + l_row;          // row of the tile, 0..63
+    k_chunk[i] = l_pos ^ (trow & 15);
+    v_chunk[i] = l_pos ^ (2 * (trow & 7));
+    k_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + k_chunk[i] * 8;
+    v_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + v_chunk[i] * 8;
+  }
+
+  __syncthreads();                       // block-table row staged
+
+  auto issue = [&](int key_tile, int stage) {
+    const bool last = key_tile == n_key_tiles - 1;
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int q = wave * IPW + i;
+      const uint16_t *gk, *gv;
+      if (!last) {
+        const int64_t blk = __builtin_amdgcn_readfirstlane(s_bt[key_tile * 4 + q / 4]);
+        gk = kglob + blk * blk_stride + k_off[i];
+        gv = vglob + blk * blk_stride + v_off[i];
+      } else {
+        // rows past the frontier may be unallocated or hold anything: they fetch the frontier row
+        // instead (finite data, weight 0 after masking)
+        const int j = min(key_tile * kBN + 4 * q + l_row, wg_max);
+        const int64_t slot = static_cast<int64_t>(s_bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
+        gk = kglob + slot * p.stride_slot + k_chunk[i] * 8;
+        gv = vglob + slot * p.stride_slot + v_chunk[i] * 8;
+      }
+      dma16(gk, &sK[stage][q * 512]);
+      dma16(gv, &sV[stage][q * 512]);
+    }
+  };
+
+  // ---- LDS read addresses (elements), constant per lane
+  int k_rd[STEPS];                      // K fragment of step st: row n of a 32-key block
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st) k_rd[st] = n * D + (((2 * st + h) ^ (n & 15)) << 3);
+  const int i16 = lane & 15, gid = (lane >> 4) & 1;
+  const int v_row = 4 * h + (i16 >> 2);                       // 0..7: row inside an 8-key group
+  const int v_swz = 2 * v_row;
+  int v_rd[DB];                          // V transpose read of d-block db: row v_row of the group
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    v_rd[db] = v_row * D + (((4 * db + 2 * gid + ((i16 & 3) >> 1)) ^ v_swz) << 3) + 4 * (i16 & 1);
+
+  auto compute = [&](int kt, int stage) {
+    const int j0 = kt * kBN;
+    const uint16_t* tK = sK[stage];
+    const uint16_t* tV = sV[stage];
+    f32x16 sacc[2];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 a = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const cs::u32x4*>(&tK[kb * 32 * D + k_rd[st]]));
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], st == 0 ? zero16 : sacc[kb], 0, 0, 0);
+      }
+    }
+    if (j0 + kBN - 1 > wave_min) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
+          if (key > lim) sacc[kb][r] = kNegInf;
+        }
+    }
+    float t_max = kNegInf;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[kb][r]);
+    t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
+    if (__any(t_max > m_run + slack)) {
+      const bool up = t_max > m_run + slack;
+      const float m_new = up ? t_max : m_run;
+      const float alpha = up ? __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e) : 1.f;
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    const float m_scaled = (m_run == kNegInf ? 0.f : m_run) * p.scale_log2e;
+    bf16x8 pb[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        cs::u32x4 w;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
+          const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
+          const uint32_t pk = pack_bf16x2(e0, e1);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
+                                                  __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run, false);
+          w[c] = pk;
+        }
+        pb[kb][mm] = __builtin_bit_cast(bf16x8, w);
+      }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        const int g0 = (32 * kb + 16 * mm) * D;             // first 8-key group of this MFMA
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + v_rd[db]]));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + 8 * D + v_rd[db]]));
+          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kb][mm],
+                                                         o[db], 0, 0, 0);
+        }
+      }
+  };
+
+  // The Q fragments must be complete before the loop: a wait for them inside it would also
+  // drain the K/V requests in flight (vector-memory operations retire in order).
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st) asm volatile("" : "+v"(qf[st]));
+
+  // ---- pipeline over this workgroup's key tiles [kt_begin, kt_end): the i-th of them lives in
+  //      stage i % NS and is requested AHEAD tiles early
+  const int n_my = kt_end - kt_begin;
+#pragma unroll
+  for (int t = 0; t < AHEAD; ++t)
+    if (t < n_my) issue(kt_begin + t, t);
+  for (int i0 = 0; i0 < n_my; i0 += NS) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+      const int i = i0 + u;
+      if (i < n_my) {
+        const int kt = kt_begin + i;
+        // this wave's share of the tile has landed once at most the requests of later tiles remain
+        const int later = min(AHEAD - 1, n_my - 1 - i);
+        if (later >= 2) wait_vmcnt<2 * 2 * IPW>();
+        else if (later == 1) wait_vmcnt<1 * 2 * IPW>();
+        else wait_vmcnt<0>();
+        __syncthreads();                   // everyone's share landed; everyone left the previous tile
+        if (i + AHEAD < n_my) issue(kt + AHEAD, (u + AHEAD) % NS);
+        if (kt * kBN <= wave_max) compute(kt, u);
+      }
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (n_split > 1) {
+    // partial result of this key range: un-normalised rows, reference maximum and row sum
+    const int64_t prow = (static_cast<int64_t>(item) * p.max_splits + split) * BM + wave * 32 + n;
+    if (h == 0) {
+      p.ws_ml[prow * 2] = m_run;
+      p.ws_ml[prow * 2 + 1] = l_tot;
+    }
+    float* po = p.ws_o + prow * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const cs::u32x4 w = {__float_as_uint(o[db][4 * rq + 0]), __float_as_uint(o[db][4 * rq + 1]),
+                             __float_as_uint(o[db][4 * rq + 2]), __float_as_uint(o[db][4 * rq + 3])};
+        *reinterpret_cast<cs::u32x4*>(po + 32 * db + 8 * rq + 4 * h) = w;
+      }
+    return;
+  }
+  if (valid) {
+    const float inv = 1.f / l_tot;
+    uint16_t* orow = static_cast<uint16_t*>(p.out) +
+                     (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        cs::u32x2 w;
+        w.x = pack_bf16x2(o[db][4 * rq + 0] * inv, o[db][4 * rq + 1] * inv);
+        w.y = pack_bf16x2(o[db][4 * rq + 2] * inv, o[db][4 * rq + 3] * inv);
+        *reinterpret_cast<cs::u32x2*>(orow + 32 * db + 8 * rq + 4 * h) = w;
+      }
+  }
+}
+
+// Merges the partial results of split row tiles: out = sum_c w_c O_c / sum_c w_c l_c with
+// w_c = 2^((m_c - max_c m_c) * scale * log2 e).  One workgroup per 8 rows; 32 threads per row.
+__global__ __launch_bounds__(256) void window_attn_merge_kernel(AttnParams p) {
+  constexpr int D = 128;
+  const int groups = p.bm / 8;
+  const int item = blockIdx.x / groups;
+  const int32_t* d = p.ws_desc + item * 8;
+  const int n_split = d[4];
+  if (n_split <= 1) return;
+  const int q0 = d[0], rows_total = d[1], r_tile = d[2], kvh = d[3];
+  const int sub = threadIdx.x & 31;                    // 4 consecutive output dims
+  const int rl = (blockIdx.x - item * groups) * 8 + (threadIdx.x >> 5);
+  const int row = r_tile + rl;
+  if (row >= rows_total) return;
+  const int64_t base = static_cast<int64_t>(item) * p.max_splits * p.bm + rl;
+  float m_all = kNegInf;
+  for (int c = 0; c < n_split; ++c) m_all = fmaxf(m_all, p.ws_ml[(base + static_cast<int64_t>(c) * p.bm) * 2]);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f}, l_all = 0.f;
+  for (int c = 0; c < n_split; ++c) {
+    const int64_t pr = base + static_cast<int64_t>(c) * p.bm;
+    const float m_c = p.ws_ml[pr * 2];
+    if (m_c == kNegInf) continue;                      // this key range held nothing visible
+    const float w = __builtin_amdgcn_exp2f((m_c - m_all) * p.scale_log2e);
+    l_all = fmaf(w, p.ws_ml[pr * 2 + 1], l_all);
+    const float4 t = *reinterpret_cast<const float4*>(p.ws_o + pr * D + 4 * sub);
+    acc[0] = fmaf(w, t.x, acc[0]); acc[1] = fmaf(w, t.y, acc[1]);
+    acc[2] = fmaf(w, t.z, acc[2]); acc[3] = fmaf(w, t.w, acc[3]);
+  }
+  const float inv = 1.f / l_all;
+  const int tok = q0 + row / p.group;
+  const int head = kvh * p.group + row % p.group;
+  uint16_t* orow = static_cast<uint16_t*>(p.out) + (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
+  cs::u32x2 w2;
+  w2.x = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+  w2.y = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+  *reinterpret_cast<cs::u32x2*>(orow + 4 * sub) = w2;
+}
+
+// ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void window_attn_f32_kernel(AttnParams p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -357,12 +744,51 @@ __global__ __launch_bounds__(256) void window_attn_f32_kernel(AttnParams p) {
   }
 }
 
+// Launch shape of the bf16 / head_dim 128 path, shared by the workspace query and the call.
+struct AttnPlan {
+  bool big;              // 256-row workgroups (8 waves) instead of 128-row ones
+  int bm;
+  int64_t items;         // upper bound on (stream, kv head, row tile) work items
+  int chunk_tiles;       // key tiles per workgroup when a row tile is split
+  int max_splits;
+  size_t desc_bytes, ml_bytes, o_bytes;
+};
+
+AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_heads, int32_t max_blocks) {
+  AttnPlan a;
+  // 256-row workgroups only pay off for long key sweeps on grids that still fill the chip
+  const int64_t tiles256 = (n_q * group) / 256 + n_streams;
+  a.big = tiles256 * n_kv_heads >= 512 && static_cast<int64_t>(max_blocks) * CS_KV_BLOCK >= 4096;
+  a.bm = a.big ? 256 : 128;
+  a.items = ((n_q * group) / a.bm + n_streams) * n_kv_heads;
+  // split long key sweeps when the row tiles alone cannot fill the chip a couple of times over
+  const int max_tiles = static_cast<int>((static_cast<int64_t>(max_blocks) * CS_KV_BLOCK + kBN - 1) / kBN);
+  const int64_t target = 1024;
+  a.chunk_tiles = 1 << 30;
+  a.max_splits = 1;
+  if (a.items < target && max_tiles > 4) {
+    const int wanted = static_cast<int>((target + a.items - 1) / a.items);
+    a.chunk_tiles = max_tiles / wanted;
+    if (a.chunk_tiles < 4) a.chunk_tiles = 4;
+    a.max_splits = (max_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
+    if (a.max_splits <= 1) { a.max_splits = 1; a.chunk_tiles = 1 << 30; }
+  }
+  a.desc_bytes = a.max_splits > 1 ? static_cast<size_t>(a.items) * 8 * sizeof(int32_t) : 0;
+  a.ml_bytes = a.max_splits > 1 ? static_cast<size_t>(a.items) * a.max_splits * a.bm * 2 * sizeof(float) : 0;
+  a.o_bytes = a.max_splits > 1 ? static_cast<size_t>(a.items) * a.max_splits * a.bm * 128 * sizeof(float) : 0;
+  return a;
+}
+
 }  // namespace
 
 extern "C" size_t cs_window_prefill_attn_workspace(int64_t n_q, int32_t n_streams, int32_t n_q_heads,
-                                                   int32_t n_kv_heads, int32_t head_dim, int32_t dtype) {
-  (void)n_q; (void)n_streams; (void)n_q_heads; (void)n_kv_heads; (void)head_dim; (void)dtype;
-  return 0;
+                                                   int32_t n_kv_heads, int32_t head_dim,
+                                                   int32_t max_blocks, int32_t dtype) {
+  if (dtype != CS_BF16 || head_dim != 128 || n_q <= 0 || n_streams <= 0 || n_kv_heads < 1 ||
+      n_q_heads < n_kv_heads || max_blocks <= 0)
+    return 0;
+  const AttnPlan a = plan_attn(n_q, n_streams, n_q_heads / n_kv_heads, n_kv_heads, max_blocks);
+  return a.desc_bytes + a.ml_bytes + a.o_bytes;
 }
 
 extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void* v_cache_layer,
@@ -372,7 +798,6 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
                                       int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
                                       int64_t stride_head, float softmax_scale, int32_t dtype,
                                       void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace; (void)workspace_bytes;
   if (n_q < 0 || n_streams < 0 || n_q_heads < 1 || n_kv_heads < 1 || max_blocks < 0) return CS_EINVAL;
   if (stride_slot < 0 || stride_head < 0) return CS_EINVAL;
   if (n_q_heads % n_kv_heads) return CS_EINVAL;
@@ -399,6 +824,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   p.cu_q = cu_q;
   p.q_pos = q_pos;
   p.block_table = block_table;
+  p.kv_len = kv_len;
   p.stride_slot = stride_slot;
   p.stride_head = stride_head;
   p.max_blocks = max_blocks;
@@ -409,18 +835,49 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   p.scale = softmax_scale;
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   p.n_q = n_q;
+  p.xcd_chunk = 0;
   hipStream_t st = cs::as_stream(stream);
   if (dtype == CS_BF16) {
-    // upper bound on the number of row tiles: sum_s ceil(n_q_s * group / 128)
-    const int64_t tiles = (n_q * group) / kBM + n_streams;
-    if (tiles > 0x7fffffffll) return CS_EUNSUPPORTED;
-    const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_kv_heads));
     if (max_blocks > kMaxBlocksInLds) return CS_EUNSUPPORTED;
     const size_t bt_bytes = static_cast<size_t>(max_blocks) * sizeof(int32_t);
-    if (head_dim == 128)
-      hipLaunchKernelGGL(window_attn_bf16_kernel<128>, grid, dim3(256), bt_bytes, st, p);
-    else
+    if (head_dim == 128) {
+      const AttnPlan a = plan_attn(n_q, n_streams, group, n_kv_heads, max_blocks);
+      p.bm = a.bm;
+      p.chunk_tiles = a.chunk_tiles;
+      p.max_splits = a.max_splits;
+      p.ws_desc = nullptr; p.ws_ml = nullptr; p.ws_o = nullptr;
+      if (a.max_splits > 1) {
+        const size_t need = a.desc_bytes + a.ml_bytes + a.o_bytes;
+        if (!workspace || workspace_bytes < need || !cs::aligned16(workspace)) return CS_EWORKSPACE;
+        char* w = static_cast<char*>(workspace);
+        p.ws_o = reinterpret_cast<float*>(w);
+        p.ws_ml = reinterpret_cast<float*>(w + a.o_bytes);
+        p.ws_desc = reinterpret_cast<int32_t*>(w + a.o_bytes + a.ml_bytes);
+      }
+      int64_t wgs = a.items * a.max_splits;
+      p.xcd_chunk = 0;
+      if (a.max_splits == 1 && static_cast<int64_t>(n_streams) * n_kv_heads >= 16) {
+        p.xcd_chunk = static_cast<int32_t>((wgs + 7) / 8);     // enough (stream, head) pairs to
+        wgs = static_cast<int64_t>(p.xcd_chunk) * 8;           // balance the 8 XCDs
+      }
+      if (wgs > 0x7fffffffll) return CS_EUNSUPPORTED;
+      const dim3 grid(static_cast<unsigned>(wgs));
+      if (a.big)
+        hipLaunchKernelGGL((window_attn_bf16_async_kernel<8, 4>), grid, dim3(512), bt_bytes, st, p);
+      else
+        hipLaunchKernelGGL((window_attn_bf16_async_kernel<4, 2>), grid, dim3(256), bt_bytes, st, p);
+      if (a.max_splits > 1) {
+        const int e = cs::note_hip(hipGetLastError());
+        if (e != CS_OK) return e;
+        hipLaunchKernelGGL(window_attn_merge_kernel, dim3(static_cast<unsigned>(a.items * (a.bm / 8))),
+                           dim3(256), 0, st, p);
+      }
+    } else {
+      const int64_t tiles = (n_q * group) / kBM + n_streams;           // upper bound on row tiles
+      if (tiles > 0x7fffffffll) return CS_EUNSUPPORTED;
+      const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_kv_heads));
       hipLaunchKernelGGL(window_attn_bf16_kernel<64>, grid, dim3(256), bt_bytes, st, p);
+    }
   } else {
     const int64_t units = n_q * n_q_heads;
     const dim3 grid(static_cast<unsigned>((units + 3) / 4));

@@ -185,7 +185,7 @@ class DeviceStep:
         self.out = torch.zeros_like(self.q)
         self.n_q = int(p.q_pos.shape[0])
         ws_d = cs.cs_window_prefill_attn_workspace(self.n_q, w.n_streams, w.n_q_heads, w.n_kv_heads,
-                                                   w.head_dim, self.dtype)
+                                                   w.head_dim, self.max_blocks, self.dtype)
         self.ws_d_bytes = ws_d
         self.ws_d = torch.zeros((max(8, ws_d),), dtype=torch.uint8, device=dev)
 

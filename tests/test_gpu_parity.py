@@ -289,8 +289,8 @@ def _attn_case(cs, rng, dtype, n_q_heads, n_kv_heads, d, kv_lens, n_qs, shuffle=
     out = torch.full((max(1, n_q), n_q_heads, d), 7.0, dtype=q.dtype, device=DEV)
     kd, vd = kc.to(DEV), vc.to(DEV)
     code = cs.CS_BF16 if dtype == "bf16" else cs.CS_F32
-    wsb = cs.cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, d, code)
-    ws = torch.zeros((max(8, wsb),), dtype=torch.uint8, device=DEV)
+    wsb = cs.cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, d, max_blocks, code)
+    ws = torch.randint(0, 255, (max(16, wsb),), dtype=torch.uint8, device=DEV)     # dirty workspace
     cs.cs_window_prefill_attn(q.to(DEV), kd, vd, torch.from_numpy(cu).to(DEV), torch.from_numpy(q_pos).to(DEV),
                               torch.tensor(kv_lens, dtype=torch.int32, device=DEV),
                               torch.from_numpy(bt).to(DEV), max_blocks, 16, out, n_q, n_streams, n_q_heads,
@@ -309,6 +309,8 @@ ATTN_CASES = [
     ("bf16", 8, 1, 128, [513], [70]),                         # 8-way group, ragged tail of one key
     ("bf16", 2, 1, 64, [1040], [18]),
     ("bf16", 28, 4, 128, [64, 65, 127, 128], [5, 9, 19, 37]),  # frontiers on tile edges
+    ("bf16", 28, 4, 128, [6033], [300]),                      # long sweep, few rows: split over keys
+    ("bf16", 8, 2, 128, [3000, 700, 40], [257, 64, 40]),      # split and unsplit row tiles in one launch
 ]
 
 
@@ -342,11 +344,13 @@ def test_attention_properties_on_gpu(cs):
     out = torch.zeros_like(q)
     args = (torch.tensor([0, n_q], dtype=torch.int32, device=DEV), q_pos,
             torch.tensor([500], dtype=torch.int32, device=DEV), bt, 32, 16)
-    cs.cs_window_prefill_attn(q, kc, vc, *args, out, n_q, 1, hq, hkv, d, hkv * d, d, 0.09, cs.CS_BF16)
+    wsb = cs.cs_window_prefill_attn_workspace(n_q, 1, hq, hkv, d, 32, cs.CS_BF16)
+    ws = torch.zeros((max(16, wsb),), dtype=torch.uint8, device=DEV)
+    cs.cs_window_prefill_attn(q, kc, vc, *args, out, n_q, 1, hq, hkv, d, hkv * d, d, 0.09, cs.CS_BF16, ws, wsb)
     torch.cuda.synchronize()
     assert torch.all(out.float() == 1.0)
     vr = _pool(rng, (512, hkv, d), "bf16").to(DEV)
-    cs.cs_window_prefill_attn(q, kc, vr, *args, out, n_q, 1, hq, hkv, d, hkv * d, d, 0.09, cs.CS_BF16)
+    cs.cs_window_prefill_attn(q, kc, vr, *args, out, n_q, 1, hq, hkv, d, hkv * d, d, 0.09, cs.CS_BF16, ws, wsb)
     torch.cuda.synchronize()
     for h in range(hq):
         assert torch.equal(out[0, h], vr[0, h // (hq // hkv)])
