@@ -38,6 +38,10 @@ def parse():
                     help="one of the synthetic workloads in paper_2604_06036_amd.synth.WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a HIP graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for HBM counters and copy bandwidth)")
+    ap.add_argument("--no-scaled-scoring", action="store_true",
+                    help="skip the scaled-batch bandwidth measurement of cs_score_compact")
     return ap.parse_args()
 
 
@@ -67,6 +71,58 @@ def event_time(torch, fn, reps):
     e1.record()
     e1.synchronize()
     return e0.elapsed_time(e1) / reps
+
+
+def copy_calibration(torch):
+    """A plain device-to-device copy of known size: 1 GiB read + 1 GiB written (larger than the
+    256 MB Infinity Cache).  Its HBM counters calibrate FETCH_SIZE / WRITE_SIZE, its rate is the
+    practical ceiling the bandwidth-bound kernels are compared with."""
+    n = 1 << 29                                             # bf16 elements = 1 GiB
+    a = torch.ones((n,), dtype=torch.bfloat16, device="cuda")
+    b = torch.empty_like(a)
+    for _ in range(2):
+        b.copy_(a)
+    ms = event_time(torch, lambda: b.copy_(a), 5)
+    return dict(bytes_read=2 * n, bytes_written=2 * n, ms=ms, GBps=4.0 * n / ms / 1e6)
+
+
+def scaled_scoring(w, torch, binding):
+    """cs_score_compact on a SCALED batch: the workload's per-stream shape (one new frame of the
+    same patch grid per stream) with the stream count raised until the metadata exceeds 256 MB, so
+    that the kernel's bandwidth rather than its launch latency is measured.  Metadata is drawn on
+    the GPU with the generator's marginals (25 % of patches moving), without the blob structure."""
+    n_patch = w.patches
+    n_streams = max(w.n_streams, (288 << 20) // (n_patch * 8))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0xC0DEC)
+    moving = torch.rand((n_streams, n_patch), generator=gen, device="cuda") < 0.25
+    sigma = torch.where(moving, 24.0, 1.0).unsqueeze(-1)
+    mv = torch.round(torch.randn((n_streams, n_patch, 2), generator=gen, device="cuda") * sigma).to(torch.int16)
+    sad = torch.round(torch.empty((n_streams, n_patch), device="cuda").exponential_(1 / 100.0, generator=gen)
+                      * torch.where(moving, 10.0, 1.0)).to(torch.int32)
+    ftype = (torch.rand((n_streams,), generator=gen, device="cuda") < 0.125).to(torch.uint8)
+    cu = torch.arange(n_streams + 1, dtype=torch.int32, device="cuda")
+    acc = (torch.rand((n_streams, n_patch), generator=gen, device="cuda") < 0.05).to(torch.uint8)
+    t_per = w.tokens_per_frame
+    keep = torch.empty((n_streams, t_per), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((n_streams * t_per,), dtype=torch.int32, device="cuda")
+    off = torch.empty((n_streams + 1,), dtype=torch.int32, device="cuda")
+    wsb = binding.cs_score_compact_workspace(n_streams, n_streams, w.grid_h, w.grid_w, w.group)
+    ws = torch.empty((wsb,), dtype=torch.uint8, device="cuda")
+    del moving, sigma
+    call = lambda: binding.cs_score_compact(mv, sad, None, ftype, cu, acc, n_streams, n_streams, w.grid_h,
+                                            w.grid_w, w.group, w.tau_mv_sq, w.tau_sad, True, keep, idx, off,
+                                            ws, wsb)
+    for _ in range(2):
+        call()
+    ms = event_time(torch, call, 5)
+    kept = int(off[-1].item())
+    p_frames = int((ftype == 0).sum().item())
+    # P-frames read MV + SAD + acc and write keep (acc writes only where it changes: not counted);
+    # I-frames write keep + acc; every kept token writes a 4-byte id; one offset per frame
+    nbytes = p_frames * n_patch * (4 + 4 + 1 + 1) + (n_streams - p_frames) * n_patch * 2 + kept * 4 + n_streams * 4
+    return dict(label="scaled batch", streams=n_streams, patches=n_streams * n_patch, kept=kept, ms=ms,
+                bytes=nbytes, GBps=nbytes / ms / 1e6, frac_of_hbm_peak=nbytes / ms / 1e6 / PEAK_HBM_GBS)
 
 
 def cpu_baseline(w, data, step, torch):
@@ -196,23 +252,29 @@ def main():
     }
     share = {k: v["ms"] * v["launches_per_step"] for k, v in kernels.items()}
     dominant = max(share, key=share.get)
-    traffic = None
+    # HBM bytes per launch of the dominant kernel, from committed rocprofv3 --pmc FETCH_SIZE /
+    # WRITE_SIZE runs of this same command, calibrated against a 1 GiB copy (profiles/): not
+    # measured live, null when no such run exists for this workload
+    traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(w.name, {}).get(dominant)
+            traffic_detail = json.load(open(tpath)).get(w.name, {}).get(dominant)
+            if traffic_detail:
+                traffic = traffic_detail["read_bytes"] + traffic_detail["write_bytes"]
         except Exception:
-            traffic = None
+            traffic, traffic_detail = None, None
     if dominant == "cs_window_prefill_attn":
         ach = kernels[dominant]["TFLOPs"]
         roofline = dict(bound="mfma", kernel="window_attn_bf16_kernel" if w.dtype == "bf16" else "window_attn_f32_kernel",
                         achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS,
-                        traffic=traffic, flops_per_launch=work["d_flops"], ms_per_launch=t_d)
+                        traffic=traffic, traffic_detail=traffic_detail, algorithmic_bytes=work["d_bytes"],
+                        flops_per_launch=work["d_flops"], ms_per_launch=t_d)
     else:
         ach = kernels[dominant]["GBps"]
         key = {"cs_score_compact": "a_bytes", "cs_kv_rerotate": "b_bytes", "cs_kv_refresh_scatter": "c_bytes"}[dominant]
         roofline = dict(bound="hbm", kernel=dominant, achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=ach / PEAK_HBM_GBS, traffic=traffic, bytes_per_launch=work[key],
+                        frac=ach / PEAK_HBM_GBS, traffic=traffic, traffic_detail=traffic_detail, bytes_per_launch=work[key],
                         ms_per_launch=kernels[dominant]["ms"])
 
     out = {
@@ -237,6 +299,10 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if args.calibrate_copy:
+        out["copy_calibration"] = copy_calibration(torch)
+    if not args.no_scaled_scoring:
+        out["score_compact_scaled"] = scaled_scoring(w, torch, binding)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, data, step, torch)
     print(json.dumps(out))

@@ -6,8 +6,9 @@
 // Work decomposition.  The accumulated mask makes frames of one stream sequentially dependent
 // but every token location is independent, so one wavefront owns one stream: its 64 lanes sweep
 // the token grid 256 locations at a time (4 coalesced 4-byte metadata loads in flight per lane)
-// and walk the stream's frames in temporal order.  A workgroup (4 waves = 4 consecutive streams)
-// is one tile of a single-pass ordered compaction:
+// and walk the stream's frames in temporal order.  A workgroup (4 waves = 4 consecutive streams,
+// or 4 runs of up to 16 consecutive streams for batches of many thousand streams) is one tile of
+// a single-pass ordered compaction:
 //   pass 1  score, write keep bytes and the accumulated state, count kept tokens by ballot;
 //   link    the tile publishes its count and obtains the number of tokens kept by all earlier
 //           tiles through a decoupled look-back over 64-bit (flag | value) words; tiles are
@@ -42,6 +43,7 @@ struct ScoreParams {
   uint32_t* error;                       // workspace word 1 (second half of the first 8 bytes)
   uint64_t* tile_state;                  // workspace + 8
   int32_t n_streams, n_frames, grid_w, tok_w, n_patch, n_tok;
+  int32_t streams_per_wave;              // consecutive streams swept by one wave (1 for small batches)
   uint32_t tau_mv_sq, tau_sad;
   int32_t use_residual;
 };
@@ -223,14 +225,13 @@ __global__ __launch_bounds__(kWavesPerTile * cs::kWave) void score_compact_kerne
   if (threadIdx.x == 0) s_ticket = atomicAdd(p.ticket, 1u);
   __syncthreads();
   const uint32_t tile = s_ticket;
-  const int s = static_cast<int>(tile) * kWavesPerTile + wave;
-  int f0 = 0, f1 = 0;
-  if (s < p.n_streams) {
-    f0 = p.cu_frames[s];
-    f1 = p.cu_frames[s + 1];
-  }
+  const int s_begin = (static_cast<int>(tile) * kWavesPerTile + wave) * p.streams_per_wave;
+  const int s_end = min(p.n_streams, s_begin + p.streams_per_wave);
   uint32_t total = 0;
-  for (int f = f0; f < f1; ++f) total += score_frame<G>(p, s, f, lane);
+  for (int s = s_begin; s < s_end; ++s) {
+    const int f0 = p.cu_frames[s], f1 = p.cu_frames[s + 1];
+    for (int f = f0; f < f1; ++f) total += score_frame<G>(p, s, f, lane);
+  }
   if (lane == 0) s_total[wave] = total;
   __syncthreads();
   if (wave == 0) {
@@ -243,14 +244,28 @@ __global__ __launch_bounds__(kWavesPerTile * cs::kWave) void score_compact_kerne
   __syncthreads();
   uint32_t base = s_exclusive;
   for (int w = 0; w < wave; ++w) base += s_total[w];
-  for (int f = f0; f < f1; ++f) {
-    if (lane == 0) p.kept_off[f] = static_cast<int32_t>(base);
-    base += emit_frame(p, f, base, lane);
+  for (int s = s_begin; s < s_end; ++s) {
+    const int f0 = p.cu_frames[s], f1 = p.cu_frames[s + 1];
+    for (int f = f0; f < f1; ++f) {
+      if (lane == 0) p.kept_off[f] = static_cast<int32_t>(base);
+      base += emit_frame(p, f, base, lane);
+    }
+    if (s == p.n_streams - 1 && lane == 0) p.kept_off[p.n_frames] = static_cast<int32_t>(base);
   }
-  if (s == p.n_streams - 1 && lane == 0) p.kept_off[p.n_frames] = static_cast<int32_t>(base);
 }
 
-inline int tiles_for(int n_streams) { return (n_streams + kWavesPerTile - 1) / kWavesPerTile; }
+// Streams per wave: one for the batches a serving step really has (all the parallelism there is);
+// for very large batches a wave sweeps several consecutive streams so that a tile carries enough
+// work to amortise its look-back and the number of tiles stays in the low thousands.
+inline int streams_per_wave_for(int n_streams) {
+  int k = (n_streams + 8191) / 8192;
+  return k < 1 ? 1 : (k > 16 ? 16 : k);
+}
+
+inline int tiles_for(int n_streams) {
+  const int per_tile = kWavesPerTile * streams_per_wave_for(n_streams);
+  return (n_streams + per_tile - 1) / per_tile;
+}
 
 }  // namespace
 
@@ -310,6 +325,7 @@ extern "C" int cs_score_compact(const int16_t* mv, const uint32_t* sad, const ui
   p.tau_mv_sq = tau_mv_sq;
   p.tau_sad = tau_sad;
   p.use_residual = use_residual ? 1 : 0;
+  p.streams_per_wave = streams_per_wave_for(n_streams);
 
   const int n_words = n_tiles + 1;
   hipLaunchKernelGGL(clear_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, st,

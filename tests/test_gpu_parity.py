@@ -120,6 +120,13 @@ def test_score_compact_many_tiles(cs):
     _score_case(cs, rng, 4096, [1] * 4096, 16, 16, 1, 400, 1100, True, True, False, p_iframe=0.1)
 
 
+def test_score_compact_waves_sweeping_several_streams(cs):
+    # above 8192 streams a wave sweeps several consecutive streams (here 3 per wave, ragged tail)
+    say("score_compact: 20011 streams with 0..2 frames each")
+    rng = np.random.default_rng(78)
+    _score_case(cs, rng, 20011, list(rng.integers(0, 3, 20011)), 8, 8, 1, 300, 1000, True, True, False)
+
+
 def test_score_compact_i_frame_ignores_metadata(cs):
     say("score_compact: garbage in I-frame metadata")
     rng = np.random.default_rng(3)
