@@ -85,6 +85,7 @@ SCORE_CASES = [
     (2, [2, 2], (6, 10), 2, 90, 300, True, False, False),
     (37, [1] * 37, (16, 16), 1, 300, 1000, True, True, False),     # 10 tiles of 4 streams
     (301, list(np.random.default_rng(5).integers(0, 4, 301)), (8, 8), 1, 250, 900, True, True, False),
+    (2, [40, 3], (16, 16), 1, 120, 700, True, True, False),          # > 128 ballot words in one wave
     (2, [3, 3], (16, 16), 1, 0, 0, True, True, False),              # zero thresholds: keep all
     (2, [3, 3], (16, 16), 1, 0xFFFFFFFF, 0xFFFFFFFF, True, False, False),   # nothing kept
 ]
