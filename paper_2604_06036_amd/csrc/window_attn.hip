@@ -463,27 +463,37 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_asy
 
   __syncthreads();                       // block-table row staged
 
+  // All DMA instructions of one wave for one tile read the same 16-slot cache block (instruction q
+  // covers tile rows 4 q .. 4 q + 3, i.e. block q / 4 of the tile's four): one table entry per wave
+  // and tile, read from LDS one tile ahead of its use so that its latency is never waited for.
+  const int bt_sub = (wave * IPW) / 4;
+  auto bt_entry = [&](int key_tile) {
+    return s_bt[min(key_tile * 4 + bt_sub, last_blk)];
+  };
+  int blk_next = 0;
   auto issue = [&](int key_tile, int stage) {
     const bool last = key_tile == n_key_tiles - 1;
+    if (!last) {
+      const int64_t base = static_cast<int64_t>(__builtin_amdgcn_readfirstlane(blk_next)) * blk_stride;
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int q = wave * IPW + i;
-      const uint16_t *gk, *gv;
-      if (!last) {
-        const int64_t blk = __builtin_amdgcn_readfirstlane(s_bt[key_tile * 4 + q / 4]);
-        gk = kglob + blk * blk_stride + k_off[i];
-        gv = vglob + blk * blk_stride + v_off[i];
-      } else {
+      for (int i = 0; i < IPW; ++i) {
+        const int q = wave * IPW + i;
+        dma16(kglob + base + k_off[i], &sK[stage][q * 512]);
+        dma16(vglob + base + v_off[i], &sV[stage][q * 512]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int q = wave * IPW + i;
         // rows past the frontier may be unallocated or hold anything: they fetch the frontier row
         // instead (finite data, weight 0 after masking)
         const int j = min(key_tile * kBN + 4 * q + l_row, wg_max);
         const int64_t slot = static_cast<int64_t>(s_bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
-        gk = kglob + slot * p.stride_slot + k_chunk[i] * 8;
-        gv = vglob + slot * p.stride_slot + v_chunk[i] * 8;
+        dma16(kglob + slot * p.stride_slot + k_chunk[i] * 8, &sK[stage][q * 512]);
+        dma16(vglob + slot * p.stride_slot + v_chunk[i] * 8, &sV[stage][q * 512]);
       }
-      dma16(gk, &sK[stage][q * 512]);
-      dma16(gv, &sV[stage][q * 512]);
     }
+    blk_next = bt_entry(key_tile + 1);
   };
 
   // ---- LDS read addresses (elements), constant per lane
@@ -504,15 +514,37 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_asy
     const uint16_t* tV = sV[stage];
     f32x16 sacc[2];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // K fragments are read two steps ahead of the MFMAs that consume them
+    constexpr int KPF = 2;
+    bf16x8 ka[KPF + 1][2];
+    auto k_frag = [&](int st, int kb) {
+      return __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(&tK[kb * 32 * D + k_rd[st]]));
+    };
+#pragma unroll
+    for (int st = 0; st < KPF; ++st) {
+      ka[st][0] = k_frag(st, 0);
+      ka[st][1] = k_frag(st, 1);
+    }
 #pragma unroll
     for (int st = 0; st < STEPS; ++st) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 a = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const cs::u32x4*>(&tK[kb * 32 * D + k_rd[st]]));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], st == 0 ? zero16 : sacc[kb], 0, 0, 0);
+      if (st + KPF < STEPS) {
+        ka[(st + KPF) % (KPF + 1)][0] = k_frag(st + KPF, 0);
+        ka[(st + KPF) % (KPF + 1)][1] = k_frag(st + KPF, 1);
       }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st % (KPF + 1)][kb], qf[st],
+                                                           st == 0 ? zero16 : sacc[kb], 0, 0, 0);
     }
+    // pin that order: 2 KPF reads up front, then two reads behind every two MFMAs (the scheduler
+    // would otherwise pull each read back to just before its use and expose the LDS latency)
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * KPF, 0);
+#pragma unroll
+    for (int st = 0; st < STEPS - KPF; ++st) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * KPF, 0);
     if (j0 + kBN - 1 > wave_min) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -581,6 +613,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_asy
   // ---- pipeline over this workgroup's key tiles [kt_begin, kt_end): the i-th of them lives in
   //      stage i % NS and is requested AHEAD tiles early
   const int n_my = kt_end - kt_begin;
+  blk_next = bt_entry(kt_begin);
 #pragma unroll
   for (int t = 0; t < AHEAD; ++t)
     if (t < n_my) issue(kt_begin + t, t);
