@@ -456,7 +456,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_asy
   for (int i = 0; i < IPW; ++i) {
     const int trow = 4 * (wave * IPW + i) + l_row;          // row of the tile, 0..63
     k_chunk[i] = l_pos ^ (trow & 15);
-    v_chunk[i] = l_pos ^ (2 * (trow & 7));
+    v_chunk[i] = l_pos ^ (4 * (trow & 3) + 2 * ((trow >> 2) & 1));
     k_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + k_chunk[i] * 8;
     v_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + v_chunk[i] * 8;
   }
@@ -502,7 +502,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_asy
   for (int st = 0; st < STEPS; ++st) k_rd[st] = n * D + (((2 * st + h) ^ (n & 15)) << 3);
   const int i16 = lane & 15, gid = (lane >> 4) & 1;
   const int v_row = 4 * h + (i16 >> 2);                       // 0..7: row inside an 8-key group
-  const int v_swz = 2 * v_row;
+  const int v_swz = 4 * (v_row & 3) + 2 * (v_row >> 2);
   int v_rd[DB];                          // V transpose read of d-block db: row v_row of the group
 #pragma unroll
   for (int db = 0; db < DB; ++db)
