@@ -242,7 +242,7 @@ def main():
     t_a = event_time(torch, step.score_compact, reps)
     t_b = event_time(torch, step.rerotate, reps)
     t_c = event_time(torch, lambda: [step.refresh_scatter(l) for l in range(L)], reps) / L
-    t_d = event_time(torch, lambda: [step.attention(l) for l in range(L)], reps) / L
+    t_d = event_time(torch, lambda: [step.attention(l, reuse_plan=l > 0) for l in range(L)], reps) / L
     kernels = {
         "cs_score_compact": dict(ms=t_a, launches_per_step=1, GBps=work["a_bytes"] / t_a / 1e6),
         "cs_kv_rerotate": dict(ms=t_b, launches_per_step=1, GBps=work["b_bytes"] / t_b / 1e6),

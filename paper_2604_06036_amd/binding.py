@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libcodecsight.so")
 
 CS_OK, CS_EINVAL, CS_EUNSUPPORTED, CS_EHIP, CS_EWORKSPACE = 0, -1, -2, -3, -4
 CS_F32, CS_BF16 = 0, 1
+CS_ATTN_PLAN_BUILD, CS_ATTN_PLAN_REUSE, CS_ATTN_PLAN_ONLY = 0, 1, 2
 CS_FRAME_P, CS_FRAME_I = 0, 1
 CS_ROPE_HALF_SPLIT, CS_ROPE_INTERLEAVED = 0, 1
 CS_KV_BLOCK = 16
@@ -69,7 +70,7 @@ def lib() -> ctypes.CDLL:
     L.cs_window_prefill_attn_workspace.argtypes = [i64, i32, i32, i32, i32, i32, i32]
     L.cs_window_prefill_attn.restype = c.c_int
     L.cs_window_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, i64, i32, i32, i32,
-                                         i32, i64, i64, f32, i32, vp, sz, vp]
+                                         i32, i64, i64, f32, i32, vp, sz, i32, vp]
     _lib = L
     return L
 
@@ -161,7 +162,8 @@ def cs_window_prefill_attn_workspace(n_q, n_streams, n_q_heads, n_kv_heads, head
 
 def cs_window_prefill_attn(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks,
                            block_size, out, n_q, n_streams, n_q_heads, n_kv_heads, head_dim, stride_slot,
-                           stride_head, softmax_scale, dtype, workspace=None, workspace_bytes=None):
+                           stride_head, softmax_scale, dtype, workspace=None, workspace_bytes=None,
+                           plan_mode=CS_ATTN_PLAN_BUILD):
     if workspace_bytes is None:
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     fn = "cs_window_prefill_attn"
@@ -174,4 +176,4 @@ def cs_window_prefill_attn(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len,
         _ptr(q), _ptr(k_cache_layer), _ptr(v_cache_layer), _ptr(cu_q), _ptr(q_pos), _ptr(kv_len),
         _ptr(block_table), max_blocks, block_size, _ptr(out), n_q, n_streams, n_q_heads, n_kv_heads,
         head_dim, stride_slot, stride_head, softmax_scale, dtype, _ptr(workspace), workspace_bytes,
-        _stream()))
+        plan_mode, _stream()))

@@ -52,6 +52,8 @@ struct AttnParams {
   // second kernel merges them (merging in the last workgroup to finish was tried and is far
   // slower here: the device-scope release/acquire it needs writes back and invalidates the L2)
   int32_t chunk_tiles, max_splits, bm;
+  const int32_t* ws_plan;   // plan header (list offsets per XCD, row-tile count, end item)
+  const int32_t* ws_items;  // item descriptors, 8 ints each, the 8 XCD lists back to back
   int32_t* ws_desc;      // [items][8]: q0, rows_total, r_tile, kvh, n_split
   float* ws_ml;          // [items][max_splits][bm][2]: running max (raw score units), row sum
   float* ws_o;           // [items][max_splits][bm][128]: un-normalised output rows
@@ -670,12 +672,595 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_asy
   }
 }
 
+// =============================================================================================
+// bf16 / head_dim 128: planned, persistent kernel
+//
+// A small planning kernel turns (cu_q, q_pos) into a list of work items, an item being one
+// (stream, kv head, 128-row tile, key range), and deals the items to the 8 XCDs: all items of one
+// (stream, kv head) pair go to one XCD (their K/V tiles then meet in that XCD's L2), pairs are
+// dealt to XCDs in boustrophedon order of decreasing work, and every XCD's list is sorted by
+// decreasing key-range length.  The plan depends only on cu_q and q_pos, so one plan serves
+// every decoder layer of a step.
+//
+// The attention kernel is persistent: workgroup b serves XCD b % 8 (workgroups are dealt to XCDs
+// round robin by the hardware) and takes the items at positions j, 2S-1-j, 2S+j, ... of that list
+// (j = b / 8, S workgroups per XCD): with a sorted list this alternation evens out the totals
+// without any run-time queue.  Its K/V tile requests run one tile ahead of the computation ACROSS
+// item boundaries, item descriptors and cache-block ids arrive through scalar loads issued a tile
+// ahead of their use, and the Q rows of the next item are requested before the finished item is
+// normalised and stored, so that the per-item latencies (descriptor -> block table -> first tile)
+// that dominate short key sweeps are paid once per workgroup instead of once per item.
+
+typedef __attribute__((ext_vector_type(8))) int32_t i32x8;
+
+// Item descriptor: 8 ints.  [0] first query token of the stream, [1] rows of the stream (tokens x
+// heads per kv group), [2] first row of the tile, [3] kv head | stream << 8, [4] highest visible
+// cache index among the tile's rows, [5],[6] key tiles [begin, end), [7] first row of the item's
+// partial result in the workspace, or -1 when the item covers the whole sweep and writes `out`.
+constexpr int kPlanHeaderInts = 32;   // [0..8] list offsets per XCD, [9] row tiles, [16..23] end item
+constexpr int kPlanThreads = 1024;
+constexpr int kSortMax = 2048;        // streams sorted by work in LDS; beyond, stream order is kept
+
+struct PlanParams {
+  const int32_t* __restrict__ cu_q;
+  const int32_t* __restrict__ q_pos;
+  int32_t n_streams, group, n_kv_heads, chunk_tiles, max_splits, max_tiles, r_cap;
+  int32_t* header;      // [kPlanHeaderInts]
+  int32_t* items;       // [items_cap][8]
+  int32_t* rt_desc;     // [r_cap * n_kv_heads][8]: q0, rows_total, r_tile, kvh, n_split
+  int32_t* st_toff;     // [n_streams + 1] first row tile of each stream
+  int32_t* st_work;     // [n_streams] key tiles summed over the stream's row tiles
+  int32_t* st_rank;     // [n_streams] rank by decreasing work
+  int32_t* rt_stream;   // [r_cap]
+  int32_t* rt_wgmax;    // [r_cap]
+  int32_t* hist;        // [8][max_tiles + 2] items per (XCD, length), then list cursors
+};
+
+// Exclusive prefix sum over the kPlanThreads threads of the planning workgroup.
+__device__ __forceinline__ int plan_block_scan(int v, int* s_wave, int& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int t = __shfl_up(incl, off);
+    if (lane >= off) incl += t;
+  }
+  __syncthreads();                       // s_wave may still be read from a previous call
+  if (lane == 63) s_wave[w] = incl;
+  __syncthreads();
+  int base = 0, sum = 0;
+  for (int i = 0; i < kPlanThreads / 64; ++i) {
+    const int t = s_wave[i];
+    if (i < w) base += t;
+    sum += t;
+  }
+  total = sum;
+  return base + incl - v;
+}
+
+__device__ __forceinline__ int plan_xcd_of_pair(int pair) {
+  const int round = pair >> 3, pos = pair & 7;
+  return (round & 1) ? 7 - pos : pos;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanParams pp) {
+  __shared__ int s_wave[kPlanThreads / 64];
+  __shared__ unsigned long long s_key[kSortMax];
+  __shared__ int s_list_off[9];
+  const int tid = threadIdx.x;
+  const int hist_pitch = pp.max_tiles + 2;
+
+  // ---- clear counters; row tiles per stream
+  for (int i = tid; i < 8 * hist_pitch; i += kPlanThreads) pp.hist[i] = 0;
+  int carry = 0;
+  for (int s0 = 0; s0 < pp.n_streams; s0 += kPlanThreads) {
+    const int s = s0 + tid;
+    int tiles = 0;
+    if (s < pp.n_streams) {
+      const int rows = (pp.cu_q[s + 1] - pp.cu_q[s]) * pp.group;
+      tiles = (rows + kBM - 1) / kBM;
+      pp.st_work[s] = 0;
+    }
+    int total;
+    const int excl = plan_block_scan(tiles, s_wave, total);
+    if (s < pp.n_streams) pp.st_toff[s] = carry + excl;
+    carry += total;
+  }
+  const int n_rt = carry;                // row tiles per kv head
+  if (tid == 0) pp.st_toff[pp.n_streams] = n_rt;
+  __threadfence_block();
+  __syncthreads();
+
+  // ---- per row tile: its stream, its causal frontier; work per stream
+  for (int r = tid; r < n_rt; r += kPlanThreads) {
+    int lo = 0, hi = pp.n_streams;       // last stream whose first row tile is <= r
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (pp.st_toff[mid] <= r) lo = mid; else hi = mid;
+    }
+    const int s = lo;
+    const int t = r - pp.st_toff[s];
+    const int q0 = pp.cu_q[s];
+    const int rows = (pp.cu_q[s + 1] - q0) * pp.group;
+    const int last_row = min((t + 1) * kBM, rows) - 1;
+    const int wg_max = pp.q_pos[q0 + last_row / pp.group];
+    pp.rt_stream[r] = s;
+    pp.rt_wgmax[r] = wg_max;
+    atomicAdd(&pp.st_work[s], wg_max / kBN + 1);
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  // ---- rank streams by decreasing work (ties: stream order)
+  if (pp.n_streams <= kSortMax) {
+    int n_sort = 1;
+    while (n_sort < pp.n_streams) n_sort <<= 1;
+    for (int i = tid; i < n_sort; i += kPlanThreads)
+      s_key[i] = i < pp.n_streams
+                     ? (static_cast<unsigned long long>(0x7fffffff - __hip_atomic_load(&pp.st_work[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) << 32) | static_cast<unsigned>(i)
+                     : ~0ull;
+    __syncthreads();
+    for (int k = 2; k <= n_sort; k <<= 1)
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        for (int i = tid; i < n_sort; i += kPlanThreads) {
+          const int partner = i ^ j;
+          if (partner > i) {
+            const unsigned long long a = s_key[i], b = s_key[partner];
+            const bool up = (i & k) == 0;
+            if ((a > b) == up) { s_key[i] = b; s_key[partner] = a; }
+          }
+        }
+        __syncthreads();
+      }
+    for (int i = tid; i < pp.n_streams; i += kPlanThreads)
+      pp.st_rank[static_cast<unsigned>(s_key[i] & 0xffffffffu)] = i;
+  } else {
+    for (int i = tid; i < pp.n_streams; i += kPlanThreads) pp.st_rank[i] = i;
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  // ---- items per (XCD, length)
+  const bool grouped = pp.n_streams * pp.n_kv_heads >= 16;
+  auto xcd_of = [&](int r, int s, int kvh, int split) {
+    return grouped ? plan_xcd_of_pair(pp.st_rank[s] * pp.n_kv_heads + kvh)
+                   : (r * pp.n_kv_heads + kvh + split) & 7;
+  };
+  for (int r = tid; r < n_rt; r += kPlanThreads) {
+    const int s = pp.rt_stream[r];
+    const int n_kt = pp.rt_wgmax[r] / kBN + 1;
+    const int n_split = pp.max_splits > 1 ? min((n_kt + pp.chunk_tiles - 1) / pp.chunk_tiles, pp.max_splits) : 1;
+    for (int kvh = 0; kvh < pp.n_kv_heads; ++kvh)
+      for (int c = 0; c < n_split; ++c) {
+        const int len = n_split > 1 ? min(pp.chunk_tiles, n_kt - c * pp.chunk_tiles) : n_kt;
+        atomicAdd(&pp.hist[xcd_of(r, s, kvh, c) * hist_pitch + min(len, pp.max_tiles + 1)], 1);
+      }
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  // ---- per XCD (one wave each): first list position of every length, longest first
+  {
+    const int w = tid >> 6, lane = tid & 63;
+    if (w < 8) {
+      int* hx = pp.hist + w * hist_pitch;
+      int run = 0;
+      for (int top = hist_pitch - 1; top >= 0; top -= 64) {
+        const int k = top - lane;                      // lane 0 takes the longest length
+        const int v = k >= 0 ? __hip_atomic_load(&hx[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const int t = __shfl_up(incl, off);
+          if (lane >= off) incl += t;
+        }
+        if (k >= 0) hx[k] = run + incl - v;
+        run += __shfl(incl, 63);
+      }
+      if (lane == 0) s_list_off[w + 1] = run;          // list length for now
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    s_list_off[0] = 0;
+    for (int x = 0; x < 8; ++x) s_list_off[x + 1] += s_list_off[x];
+    for (int x = 0; x < 9; ++x) pp.header[x] = s_list_off[x];
+    pp.header[9] = n_rt * pp.n_kv_heads;
+    for (int i = 10; i < kPlanHeaderInts; ++i) pp.header[i] = 0;
+    pp.header[16 + 4] = -1;                             // end item: no key tiles, nothing visible
+    pp.header[16 + 7] = -1;
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  // ---- write the items
+  for (int r = tid; r < n_rt; r += kPlanThreads) {
+    const int s = pp.rt_stream[r];
+    const int t = r - pp.st_toff[s];
+    const int q0 = pp.cu_q[s];
+    const int rows = (pp.cu_q[s + 1] - q0) * pp.group;
+    const int wg_max = pp.rt_wgmax[r];
+    const int n_kt = wg_max / kBN + 1;
+    const int n_split = pp.max_splits > 1 ? min((n_kt + pp.chunk_tiles - 1) / pp.chunk_tiles, pp.max_splits) : 1;
+    for (int kvh = 0; kvh < pp.n_kv_heads; ++kvh) {
+      const int rt_id = r * pp.n_kv_heads + kvh;
+      int32_t* rd = pp.rt_desc + static_cast<int64_t>(rt_id) * 8;
+      rd[0] = q0; rd[1] = rows; rd[2] = t * kBM; rd[3] = kvh; rd[4] = n_split;
+      for (int c = 0; c < n_split; ++c) {
+        const int kb = n_split > 1 ? c * pp.chunk_tiles : 0;
+        const int ke = n_split > 1 ? min(n_kt, kb + pp.chunk_tiles) : n_kt;
+        const int x = xcd_of(r, s, kvh, c);
+        const int pos = s_list_off[x] + atomicAdd(&pp.hist[x * hist_pitch + min(ke - kb, pp.max_tiles + 1)], 1);
+        int32_t* it = pp.items + static_cast<int64_t>(pos) * 8;
+        it[0] = q0; it[1] = rows; it[2] = t * kBM; it[3] = kvh | (s << 8); it[4] = wg_max;
+        it[5] = kb; it[6] = ke;
+        it[7] = n_split > 1 ? (rt_id * pp.max_splits + c) * kBM : -1;
+      }
+    }
+  }
+}
+
+// Scalar loads issued by hand: the results are uniform, travel outside the vector-memory queue
+// (so waiting for them never drains tile requests) and are only read after the explicit wait.
+__device__ __forceinline__ i32x8 sload8(const void* ptr) {
+  i32x8 v;
+  asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=&s"(v) : "s"(ptr));
+  return v;
+}
+__device__ __forceinline__ int32_t sload1(const void* ptr) {
+  int32_t v;
+  asm volatile("s_load_dword %0, %1, 0x0" : "=&s"(v) : "s"(ptr));
+  return v;
+}
+
+__global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnParams p) {
+  constexpr int D = 128;
+  constexpr int STEPS = D / 16, DB = D / 32;
+  constexpr int TILE = kBN * D;         // elements of one K (or V) tile: 16 KiB, unpadded
+  constexpr int IPW = 4;                // 1-KiB DMA instructions per wave, per tile, per tensor
+
+  __shared__ __attribute__((aligned(1024))) uint16_t sK[2][TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t sV[2][TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, h = lane >> 5;
+
+  // ---- this workgroup's items: positions j, 2S-1-j, 2S+j, ... of its XCD's list
+  const int xcd = blockIdx.x & 7, slot_j = blockIdx.x >> 3, n_slots = gridDim.x >> 3;
+  const int list_begin = p.ws_plan[xcd];
+  const int list_len = p.ws_plan[xcd + 1] - list_begin;
+  auto desc_ptr = [&](int i) -> const int32_t* {
+    const int idx = i * n_slots + ((i & 1) ? n_slots - 1 - slot_j : slot_j);
+    return idx < list_len ? p.ws_items + static_cast<int64_t>(list_begin + idx) * 8 : p.ws_plan + 16;
+  };
+  i32x8 d0 = sload8(desc_ptr(0)), d1 = sload8(desc_ptr(1)), d2 = sload8(desc_ptr(2));
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d0), "+s"(d1), "+s"(d2));
+  if (d0[6] == 0) return;               // the list is shorter than the grid
+  int seq0 = 0;                         // d0 is the seq0-th item of this workgroup
+
+  // ---- constants of the lane: DMA sources inside a cache block, LDS read addresses
+  const uint16_t* kall = static_cast<const uint16_t*>(p.k);
+  const uint16_t* vall = static_cast<const uint16_t*>(p.v);
+  const int64_t blk_stride = static_cast<int64_t>(CS_KV_BLOCK) * p.stride_slot;
+  const int l_row = lane >> 4, l_pos = lane & 15;
+  int64_t k_off[IPW], v_off[IPW];
+  int k_chunk[IPW], v_chunk[IPW];
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int trow = 4 * (wave * IPW + i) + l_row;          // row of the tile, 0..63
+    k_chunk[i] = l_pos ^ (trow & 15);
+    v_chunk[i] = l_pos ^ (4 * (trow & 3) + 2 * ((trow >> 2) & 1));
+    k_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + k_chunk[i] * 8;
+    v_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + v_chunk[i] * 8;
+  }
+  int k_rd[STEPS];
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st) k_rd[st] = n * D + (((2 * st + h) ^ (n & 15)) << 3);
+  const int i16 = lane & 15, gid = (lane >> 4) & 1;
+  const int v_row = 4 * h + (i16 >> 2);
+  const int v_swz = 4 * (v_row & 3) + 2 * (v_row >> 2);
+  int v_rd[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    v_rd[db] = v_row * D + (((4 * db + 2 * gid + ((i16 & 3) >> 1)) ^ v_swz) << 3) + 4 * (i16 & 1);
+
+  // ---- a slot of the tile stream: one key tile of one item, with the cache-block ids its
+  //      request needs (this wave's quarter of the tile, and the block of the item's frontier)
+  struct Slot {
+    int kt, ke, kvh, stream, wg_max, seq;
+    int id, last_id;
+    int live;            // an int: a bool would leave tail padding that struct copies drag through memory
+  };
+  auto first_slot = [&](const i32x8& d, int seq) {
+    Slot s;
+    s.kt = d[5]; s.ke = d[6]; s.kvh = d[3] & 255; s.stream = d[3] >> 8; s.wg_max = d[4]; s.seq = seq;
+    s.id = 0; s.last_id = 0;
+    s.live = d[6] > 0 ? 1 : 0;
+    return s;
+  };
+  auto successor = [&](const Slot& c) {
+    if (c.kt + 1 < c.ke) {
+      Slot s = c;
+      s.kt = c.kt + 1;
+      return s;
+    }
+    const int rel = c.seq + 1 - seq0;                       // 1 or 2
+    return first_slot(rel == 1 ? d1 : d2, c.seq + 1);
+  };
+  auto request_ids = [&](Slot& s) {
+    const int32_t* row = p.block_table + static_cast<int64_t>(s.stream) * p.max_blocks;
+    const int last_blk = max(s.wg_max, 0) / CS_KV_BLOCK;
+    s.id = sload1(row + min(s.kt * 4 + wave, last_blk));
+    s.last_id = sload1(row + last_blk);
+  };
+  auto issue = [&](const Slot& s, int stage) {
+    const uint16_t* kg = kall + static_cast<int64_t>(s.kvh) * p.stride_head;
+    const uint16_t* vg = vall + static_cast<int64_t>(s.kvh) * p.stride_head;
+    if (s.kt != s.wg_max / kBN) {
+      const int64_t base = static_cast<int64_t>(s.id) * blk_stride;
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int q = wave * IPW + i;
+        dma16(kg + base + k_off[i], &sK[stage][q * 512]);
+        dma16(vg + base + v_off[i], &sV[stage][q * 512]);
+      }
+    } else {
+      // the tile that holds the frontier: rows past it may be unallocated or hold anything, they
+      // fetch the frontier row instead (finite data, weight 0 after masking)
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int q = wave * IPW + i;
+        const int j_un = s.kt * kBN + 4 * q + l_row;
+        const bool over = j_un > s.wg_max;
+        const int j = over ? s.wg_max : j_un;
+        const int64_t slot = static_cast<int64_t>(over ? s.last_id : s.id) * CS_KV_BLOCK + j % CS_KV_BLOCK;
+        dma16(kg + slot * p.stride_slot + k_chunk[i] * 8, &sK[stage][q * 512]);
+        dma16(vg + slot * p.stride_slot + v_chunk[i] * 8, &sV[stage][q * 512]);
+      }
+    }
+  };
+
+  // ---- per-item state of the lane
+  bf16x8 qf[STEPS];
+  int lim_raw = 0;
+  int it_tok_head = 0, it_part = -1;
+  bool it_valid = false;
+  int it_rows_left = 0;                 // rows of the stream at and after this wave's first row
+  auto load_item = [&](const i32x8& d) {
+    const int row = d[2] + wave * 32 + n;
+    it_valid = row < d[1];
+    const int row_c = it_valid ? row : d[1] - 1;
+    const int tq = row_c / p.group;
+    const int tok = d[0] + tq;
+    it_tok_head = tok * p.n_q_heads + (d[3] & 255) * p.group + (row_c - tq * p.group);
+    it_part = d[7];
+    it_rows_left = d[1] - (d[2] + wave * 32);
+    const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + static_cast<int64_t>(it_tok_head) * D;
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st)
+      qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(qrow + 16 * st + 8 * h));
+    lim_raw = p.q_pos[tok];
+  };
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = kNegInf, l_run = 0.f;
+  const float slack = kMaxSlack / p.scale_log2e;
+  int lim = -1, wave_min = -1, wave_max = -1;
+
+  auto compute = [&](int kt, int stage) {
+    const int j0 = kt * kBN;
+    const uint16_t* tK = sK[stage];
+    const uint16_t* tV = sV[stage];
+    f32x16 sacc[2];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    constexpr int KPF = 2;               // K fragments are read two steps ahead of their MFMAs
+    bf16x8 ka[KPF + 1][2];
+    auto k_frag = [&](int st, int kb) {
+      return __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(&tK[kb * 32 * D + k_rd[st]]));
+    };
+#pragma unroll
+    for (int st = 0; st < KPF; ++st) {
+      ka[st][0] = k_frag(st, 0);
+      ka[st][1] = k_frag(st, 1);
+    }
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+      if (st + KPF < STEPS) {
+        ka[(st + KPF) % (KPF + 1)][0] = k_frag(st + KPF, 0);
+        ka[(st + KPF) % (KPF + 1)][1] = k_frag(st + KPF, 1);
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st % (KPF + 1)][kb], qf[st],
+                                                           st == 0 ? zero16 : sacc[kb], 0, 0, 0);
+    }
+    // pin that order (the scheduler would otherwise pull each read back to just before its use)
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * KPF, 0);
+#pragma unroll
+    for (int st = 0; st < STEPS - KPF; ++st) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * KPF, 0);
+    if (j0 + kBN - 1 > wave_min) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
+          if (key > lim) sacc[kb][r] = kNegInf;
+        }
+    }
+    float t_max = kNegInf;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[kb][r]);
+    t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
+    if (__any(t_max > m_run + slack)) {
+      const bool up = t_max > m_run + slack;
+      const float m_new = up ? t_max : m_run;
+      const float alpha = up ? __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e) : 1.f;
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    const float m_scaled = (m_run == kNegInf ? 0.f : m_run) * p.scale_log2e;
+    bf16x8 pb[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        cs::u32x4 w;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
+          const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
+          const uint32_t pk = pack_bf16x2(e0, e1);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
+                                                  __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run, false);
+          w[c] = pk;
+        }
+        pb[kb][mm] = __builtin_bit_cast(bf16x8, w);
+      }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        const int g0 = (32 * kb + 16 * mm) * D;             // first 8-key group of this MFMA
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + v_rd[db]]));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + 8 * D + v_rd[db]]));
+          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kb][mm],
+                                                         o[db], 0, 0, 0);
+        }
+      }
+  };
+
+  // Normalises and stores the rows of the finished item (or its un-normalised partial rows when
+  // the key sweep is shared), then clears the accumulators.
+  auto finish_item = [&](int tok_head, bool valid, int part) {
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (part >= 0) {
+      const int64_t prow = static_cast<int64_t>(part) + wave * 32 + n;
+      if (h == 0) {
+        p.ws_ml[prow * 2] = m_run;
+        p.ws_ml[prow * 2 + 1] = l_tot;
+      }
+      float* po = p.ws_o + prow * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const cs::u32x4 w = {__float_as_uint(o[db][4 * rq + 0]), __float_as_uint(o[db][4 * rq + 1]),
+                               __float_as_uint(o[db][4 * rq + 2]), __float_as_uint(o[db][4 * rq + 3])};
+          *reinterpret_cast<cs::u32x4*>(po + 32 * db + 8 * rq + 4 * h) = w;
+        }
+    } else if (valid) {
+      const float inv = 1.f / l_tot;
+      uint16_t* orow = static_cast<uint16_t*>(p.out) + static_cast<int64_t>(tok_head) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          cs::u32x2 w;
+          w.x = pack_bf16x2(o[db][4 * rq + 0] * inv, o[db][4 * rq + 1] * inv);
+          w.y = pack_bf16x2(o[db][4 * rq + 2] * inv, o[db][4 * rq + 3] * inv);
+          *reinterpret_cast<cs::u32x2*>(orow + 32 * db + 8 * rq + 4 * h) = w;
+        }
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    m_run = kNegInf;
+    l_run = 0.f;
+  };
+
+  // ---- prologue: first item, first tile request, block ids of the second slot
+  Slot cur = first_slot(d0, 0);
+  request_ids(cur);
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(cur.id), "+s"(cur.last_id));
+  issue(cur, 0);
+  Slot nxt = successor(cur);
+  request_ids(nxt);
+  load_item(d0);
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nxt.id), "+s"(nxt.last_id));
+  bool new_item = true, ep_pending = false, ep_valid = false;
+  int ep_tok_head = 0, ep_part = -1;
+  int stage = 0;
+
+  for (;;) {
+    // everything requested so far has landed: the tile of `cur`, and at an item boundary the Q
+    // rows and frontier of its item (telling the compiler so here keeps it from waiting for them
+    // later, when that wait would also cover the tile request issued below)
+    wait_vmcnt<0>();
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) asm volatile("" : "+v"(qf[st]));
+    asm volatile("" : "+v"(lim_raw));
+    __syncthreads();                     // every wave's share landed; every wave left the other stage
+    if (nxt.live) issue(nxt, stage ^ 1);
+
+    // scalar requests for later steps: block ids of the slot after next; at the last tile of an
+    // item also the descriptor three items ahead
+    const bool cur_last = cur.kt + 1 == cur.ke;
+    // (always issued, towards harmless addresses when there is nothing to fetch: a conditional
+    // request would let the compiler merge the pending register with another value before the wait)
+    Slot nn = nxt.live ? successor(nxt) : nxt;
+    request_ids(nn);
+    i32x8 d3 = sload8(cur_last ? desc_ptr(seq0 + 3) : p.ws_plan + 16);
+
+    if (ep_pending) {
+      finish_item(ep_tok_head, ep_valid, ep_part);
+      ep_pending = false;
+    }
+    if (new_item) {
+      lim = it_valid ? lim_raw : -1;
+      const int rows_here = min(32, it_rows_left);        // rows of this wave that exist
+      wave_min = rows_here > 0 ? __builtin_amdgcn_readlane(lim, 0) : -1;
+      wave_max = rows_here > 0 ? __builtin_amdgcn_readlane(lim, max(rows_here, 1) - 1) : -1;
+      new_item = false;
+    }
+    if (cur.kt * kBN <= wave_max) compute(cur.kt, stage);
+
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nn.id), "+s"(nn.last_id), "+s"(d3));
+    if (cur_last) {
+      ep_pending = true;
+      ep_tok_head = it_tok_head;
+      ep_valid = it_valid;
+      ep_part = it_part;
+      if (d1[6] > 0) {
+        load_item(d1);
+        new_item = true;
+      }
+      d0 = d1; d1 = d2; d2 = d3;
+      ++seq0;
+    }
+    if (!nxt.live) break;
+    cur = nxt;
+    nxt = nn;
+    stage ^= 1;
+  }
+  finish_item(ep_tok_head, ep_valid, ep_part);
+}
+
 // Merges the partial results of split row tiles: out = sum_c w_c O_c / sum_c w_c l_c with
 // w_c = 2^((m_c - max_c m_c) * scale * log2 e).  One workgroup per 8 rows; 32 threads per row.
 __global__ __launch_bounds__(256) void window_attn_merge_kernel(AttnParams p) {
   constexpr int D = 128;
   const int groups = p.bm / 8;
   const int item = blockIdx.x / groups;
+  if (item >= p.ws_plan[9]) return;
   const int32_t* d = p.ws_desc + item * 8;
   const int n_split = d[4];
   if (n_split <= 1) return;
@@ -777,38 +1362,56 @@ __global__ __launch_bounds__(256) void window_attn_f32_kernel(AttnParams p) {
   }
 }
 
-// Launch shape of the bf16 / head_dim 128 path, shared by the workspace query and the call.
+// Launch shape and workspace layout of the bf16 / head_dim 128 path, shared by the workspace
+// query and the call.
 struct AttnPlan {
-  bool big;              // 256-row workgroups (8 waves) instead of 128-row ones
-  int bm;
-  int64_t items;         // upper bound on (stream, kv head, row tile) work items
-  int chunk_tiles;       // key tiles per workgroup when a row tile is split
-  int max_splits;
-  size_t desc_bytes, ml_bytes, o_bytes;
+  int64_t r_cap;         // upper bound on row tiles per kv head
+  int64_t rt_cap;        // ... times kv heads
+  int64_t items_cap;     // upper bound on work items
+  int chunk_tiles;       // key tiles per item when a row tile's sweep is split
+  int max_splits, max_tiles;
+  int grid;              // persistent workgroups: 8 XCDs x up to 64
+  size_t off_items, off_rt_desc, off_st_toff, off_st_work, off_st_rank, off_rt_stream, off_rt_wgmax,
+      off_hist, off_ml, off_o, total;
 };
 
 AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_heads, int32_t max_blocks) {
   AttnPlan a;
-  // 256-row workgroups only pay off for long key sweeps on grids that still fill the chip
-  const int64_t tiles256 = (n_q * group) / 256 + n_streams;
-  a.big = tiles256 * n_kv_heads >= 512 && static_cast<int64_t>(max_blocks) * CS_KV_BLOCK >= 4096;
-  a.bm = a.big ? 256 : 128;
-  a.items = ((n_q * group) / a.bm + n_streams) * n_kv_heads;
+  a.r_cap = (n_q * group) / kBM + n_streams;
+  a.rt_cap = a.r_cap * n_kv_heads;
+  a.max_tiles = static_cast<int>((static_cast<int64_t>(max_blocks) * CS_KV_BLOCK + kBN - 1) / kBN);
   // split long key sweeps when the row tiles alone cannot fill the chip a couple of times over
-  const int max_tiles = static_cast<int>((static_cast<int64_t>(max_blocks) * CS_KV_BLOCK + kBN - 1) / kBN);
   const int64_t target = 1024;
   a.chunk_tiles = 1 << 30;
   a.max_splits = 1;
-  if (a.items < target && max_tiles > 4) {
-    const int wanted = static_cast<int>((target + a.items - 1) / a.items);
-    a.chunk_tiles = max_tiles / wanted;
+  if (a.rt_cap < target && a.max_tiles > 4) {
+    const int wanted = static_cast<int>((target + a.rt_cap - 1) / a.rt_cap);
+    a.chunk_tiles = a.max_tiles / wanted;
     if (a.chunk_tiles < 4) a.chunk_tiles = 4;
-    a.max_splits = (max_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
+    a.max_splits = (a.max_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
     if (a.max_splits <= 1) { a.max_splits = 1; a.chunk_tiles = 1 << 30; }
   }
-  a.desc_bytes = a.max_splits > 1 ? static_cast<size_t>(a.items) * 8 * sizeof(int32_t) : 0;
-  a.ml_bytes = a.max_splits > 1 ? static_cast<size_t>(a.items) * a.max_splits * a.bm * 2 * sizeof(float) : 0;
-  a.o_bytes = a.max_splits > 1 ? static_cast<size_t>(a.items) * a.max_splits * a.bm * 128 * sizeof(float) : 0;
+  a.items_cap = a.rt_cap * a.max_splits;
+  const int64_t per_xcd = (a.items_cap + 7) / 8;
+  a.grid = 8 * static_cast<int>(per_xcd < 64 ? per_xcd : 64);
+  size_t at = kPlanHeaderInts * sizeof(int32_t);
+  auto take = [&](size_t bytes) {
+    const size_t here = (at + 255) & ~static_cast<size_t>(255);
+    at = here + bytes;
+    return here;
+  };
+  a.off_items = take(static_cast<size_t>(a.items_cap) * 8 * sizeof(int32_t));
+  a.off_rt_desc = take(static_cast<size_t>(a.rt_cap) * 8 * sizeof(int32_t));
+  a.off_st_toff = take((static_cast<size_t>(n_streams) + 1) * sizeof(int32_t));
+  a.off_st_work = take(static_cast<size_t>(n_streams) * sizeof(int32_t));
+  a.off_st_rank = take(static_cast<size_t>(n_streams) * sizeof(int32_t));
+  a.off_rt_stream = take(static_cast<size_t>(a.r_cap) * sizeof(int32_t));
+  a.off_rt_wgmax = take(static_cast<size_t>(a.r_cap) * sizeof(int32_t));
+  a.off_hist = take(static_cast<size_t>(8) * (a.max_tiles + 2) * sizeof(int32_t));
+  const bool split = a.max_splits > 1;
+  a.off_ml = take(split ? static_cast<size_t>(a.items_cap) * kBM * 2 * sizeof(float) : 0);
+  a.off_o = take(split ? static_cast<size_t>(a.items_cap) * kBM * 128 * sizeof(float) : 0);
+  a.total = (at + 255) & ~static_cast<size_t>(255);
   return a;
 }
 
@@ -820,8 +1423,8 @@ extern "C" size_t cs_window_prefill_attn_workspace(int64_t n_q, int32_t n_stream
   if (dtype != CS_BF16 || head_dim != 128 || n_q <= 0 || n_streams <= 0 || n_kv_heads < 1 ||
       n_q_heads < n_kv_heads || max_blocks <= 0)
     return 0;
-  const AttnPlan a = plan_attn(n_q, n_streams, n_q_heads / n_kv_heads, n_kv_heads, max_blocks);
-  return a.desc_bytes + a.ml_bytes + a.o_bytes;
+  if (n_q_heads % n_kv_heads || n_q * n_q_heads >= (1ll << 31)) return 0;
+  return plan_attn(n_q, n_streams, n_q_heads / n_kv_heads, n_kv_heads, max_blocks).total;
 }
 
 extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void* v_cache_layer,
@@ -830,7 +1433,8 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
                                       void* out, int64_t n_q, int32_t n_streams, int32_t n_q_heads,
                                       int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
                                       int64_t stride_head, float softmax_scale, int32_t dtype,
-                                      void* workspace, size_t workspace_bytes, void* stream) {
+                                      void* workspace, size_t workspace_bytes, int32_t plan_mode,
+                                      void* stream) {
   if (n_q < 0 || n_streams < 0 || n_q_heads < 1 || n_kv_heads < 1 || max_blocks < 0) return CS_EINVAL;
   if (stride_slot < 0 || stride_head < 0) return CS_EINVAL;
   if (n_q_heads % n_kv_heads) return CS_EINVAL;
@@ -842,8 +1446,9 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   const int elems = dtype == CS_BF16 ? 8 : 4;
   if (stride_slot % elems || stride_head % elems) return CS_EUNSUPPORTED;
   if (n_q == 0 || n_streams == 0) return CS_OK;
-  if (!q || !k_cache_layer || !v_cache_layer || !cu_q || !q_pos || !kv_len || !block_table || !out)
-    return CS_EINVAL;
+  const bool plan_only = plan_mode == CS_ATTN_PLAN_ONLY && dtype == CS_BF16 && head_dim == 128;
+  if (!cu_q || !q_pos || !kv_len || !block_table) return CS_EINVAL;
+  if (!plan_only && (!q || !k_cache_layer || !v_cache_layer || !out)) return CS_EINVAL;
   if (!cs::aligned16(q) || !cs::aligned16(out) || !cs::aligned16(k_cache_layer) ||
       !cs::aligned16(v_cache_layer))
     return CS_EUNSUPPORTED;
@@ -871,41 +1476,57 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   p.xcd_chunk = 0;
   hipStream_t st = cs::as_stream(stream);
   if (dtype == CS_BF16) {
-    if (max_blocks > kMaxBlocksInLds) return CS_EUNSUPPORTED;
     const size_t bt_bytes = static_cast<size_t>(max_blocks) * sizeof(int32_t);
     if (head_dim == 128) {
+      if (n_kv_heads > 256 || n_streams >= (1 << 23)) return CS_EUNSUPPORTED;
+      if (plan_mode != CS_ATTN_PLAN_BUILD && plan_mode != CS_ATTN_PLAN_REUSE && plan_mode != CS_ATTN_PLAN_ONLY)
+        return CS_EINVAL;
       const AttnPlan a = plan_attn(n_q, n_streams, group, n_kv_heads, max_blocks);
-      p.bm = a.bm;
+      if (a.items_cap * kBM >= (1ll << 31)) return CS_EUNSUPPORTED;
+      if (!workspace || workspace_bytes < a.total || !cs::aligned16(workspace)) return CS_EWORKSPACE;
+      char* w = static_cast<char*>(workspace);
+      p.bm = kBM;
       p.chunk_tiles = a.chunk_tiles;
       p.max_splits = a.max_splits;
-      p.ws_desc = nullptr; p.ws_ml = nullptr; p.ws_o = nullptr;
-      if (a.max_splits > 1) {
-        const size_t need = a.desc_bytes + a.ml_bytes + a.o_bytes;
-        if (!workspace || workspace_bytes < need || !cs::aligned16(workspace)) return CS_EWORKSPACE;
-        char* w = static_cast<char*>(workspace);
-        p.ws_o = reinterpret_cast<float*>(w);
-        p.ws_ml = reinterpret_cast<float*>(w + a.o_bytes);
-        p.ws_desc = reinterpret_cast<int32_t*>(w + a.o_bytes + a.ml_bytes);
+      p.ws_plan = reinterpret_cast<const int32_t*>(w);
+      p.ws_items = reinterpret_cast<const int32_t*>(w + a.off_items);
+      p.ws_desc = reinterpret_cast<int32_t*>(w + a.off_rt_desc);
+      p.ws_ml = reinterpret_cast<float*>(w + a.off_ml);
+      p.ws_o = reinterpret_cast<float*>(w + a.off_o);
+      if (plan_mode != CS_ATTN_PLAN_REUSE) {
+        PlanParams pp;
+        pp.cu_q = cu_q;
+        pp.q_pos = q_pos;
+        pp.n_streams = n_streams;
+        pp.group = group;
+        pp.n_kv_heads = n_kv_heads;
+        pp.chunk_tiles = a.chunk_tiles;
+        pp.max_splits = a.max_splits;
+        pp.max_tiles = a.max_tiles;
+        pp.r_cap = static_cast<int32_t>(a.r_cap);
+        pp.header = reinterpret_cast<int32_t*>(w);
+        pp.items = reinterpret_cast<int32_t*>(w + a.off_items);
+        pp.rt_desc = reinterpret_cast<int32_t*>(w + a.off_rt_desc);
+        pp.st_toff = reinterpret_cast<int32_t*>(w + a.off_st_toff);
+        pp.st_work = reinterpret_cast<int32_t*>(w + a.off_st_work);
+        pp.st_rank = reinterpret_cast<int32_t*>(w + a.off_st_rank);
+        pp.rt_stream = reinterpret_cast<int32_t*>(w + a.off_rt_stream);
+        pp.rt_wgmax = reinterpret_cast<int32_t*>(w + a.off_rt_wgmax);
+        pp.hist = reinterpret_cast<int32_t*>(w + a.off_hist);
+        hipLaunchKernelGGL(window_attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, pp);
+        const int e = cs::note_hip(hipGetLastError());
+        if (e != CS_OK) return e;
+        if (plan_mode == CS_ATTN_PLAN_ONLY) return CS_OK;
       }
-      int64_t wgs = a.items * a.max_splits;
-      p.xcd_chunk = 0;
-      if (a.max_splits == 1 && static_cast<int64_t>(n_streams) * n_kv_heads >= 16) {
-        p.xcd_chunk = static_cast<int32_t>((wgs + 7) / 8);     // enough (stream, head) pairs to
-        wgs = static_cast<int64_t>(p.xcd_chunk) * 8;           // balance the 8 XCDs
-      }
-      if (wgs > 0x7fffffffll) return CS_EUNSUPPORTED;
-      const dim3 grid(static_cast<unsigned>(wgs));
-      if (a.big)
-        hipLaunchKernelGGL((window_attn_bf16_async_kernel<8, 4>), grid, dim3(512), bt_bytes, st, p);
-      else
-        hipLaunchKernelGGL((window_attn_bf16_async_kernel<4, 2>), grid, dim3(256), bt_bytes, st, p);
+      hipLaunchKernelGGL(window_attn_bf16_stream_kernel, dim3(static_cast<unsigned>(a.grid)), dim3(256), 0, st, p);
       if (a.max_splits > 1) {
         const int e = cs::note_hip(hipGetLastError());
         if (e != CS_OK) return e;
-        hipLaunchKernelGGL(window_attn_merge_kernel, dim3(static_cast<unsigned>(a.items * (a.bm / 8))),
+        hipLaunchKernelGGL(window_attn_merge_kernel, dim3(static_cast<unsigned>(a.rt_cap * (kBM / 8))),
                            dim3(256), 0, st, p);
       }
     } else {
+      if (max_blocks > kMaxBlocksInLds) return CS_EUNSUPPORTED;
       const int64_t tiles = (n_q * group) / kBM + n_streams;           // upper bound on row tiles
       if (tiles > 0x7fffffffll) return CS_EUNSUPPORTED;
       const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_kv_heads));

@@ -210,14 +210,17 @@ class DeviceStep:
                                       self.k_pool[layer], self.v_pool[layer], self.n_q, w.n_kv_heads,
                                       w.head_dim, self.stride_slot, self.stride_head, self.dtype)
 
-    def attention(self, layer: int):
+    def attention(self, layer: int, reuse_plan: bool = False):
+        """Attention of one layer.  The work plan depends only on cu_q / q_pos: `run` builds it at
+        the first layer and lets the other layers reuse it."""
         w = self.data.workload
         self.cs.cs_window_prefill_attn(self.q[layer], self.k_pool[layer], self.v_pool[layer], self.cu_q,
                                        self.q_pos, self.kv_len, self.block_table, self.max_blocks,
                                        self.cs.CS_KV_BLOCK, self.out[layer], self.n_q, w.n_streams,
                                        w.n_q_heads, w.n_kv_heads, w.head_dim, self.stride_slot,
                                        self.stride_head, self.data.softmax_scale, self.dtype,
-                                       self.ws_d if self.ws_d_bytes else None, self.ws_d_bytes)
+                                       self.ws_d if self.ws_d_bytes else None, self.ws_d_bytes,
+                                       self.cs.CS_ATTN_PLAN_REUSE if reuse_plan else self.cs.CS_ATTN_PLAN_BUILD)
 
     def run(self):
         """One pass of the whole hot path."""
@@ -225,4 +228,4 @@ class DeviceStep:
         self.rerotate()
         for layer in range(self.data.workload.n_layers):
             self.refresh_scatter(layer)
-            self.attention(layer)
+            self.attention(layer, reuse_plan=layer > 0)
