@@ -331,6 +331,29 @@ __device__ __forceinline__ void dma16(const void* gsrc, const void* lds_dst) {
                : "memory", "m0");
 }
 
+// The same with a wave-uniform 64-bit base in SGPRs and a 32-bit byte offset per lane.
+__device__ __forceinline__ void dma16_s(uint32_t off, const void* sbase, const void* lds_dst) {
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)lds_dst));
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(off), "s"(sbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+// ... and under a wave-uniform predicate applied through the execution mask (mask 0: the
+// instruction issues with no lane active and moves nothing), so that a request can be interleaved
+// with a block of MFMAs without a branch splitting that block.
+__device__ __forceinline__ void dma16_s_if(uint64_t mask, uint32_t off, const void* sbase, const void* lds_dst) {
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)lds_dst));
+  uint64_t saved;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\ts_and_b64 exec, exec, %4\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0"
+      : "=&s"(saved)
+      : "v"(off), "s"(sbase), "s"(lds_addr), "s"(mask)
+      : "memory", "m0", "scc");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
@@ -944,15 +967,15 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
   const uint16_t* vall = static_cast<const uint16_t*>(p.v);
   const int64_t blk_stride = static_cast<int64_t>(CS_KV_BLOCK) * p.stride_slot;
   const int l_row = lane >> 4, l_pos = lane & 15;
-  int64_t k_off[IPW], v_off[IPW];
+  uint32_t k_off[IPW], v_off[IPW];      // byte offsets inside a cache block (the host checks the range)
   int k_chunk[IPW], v_chunk[IPW];
 #pragma unroll
   for (int i = 0; i < IPW; ++i) {
     const int trow = 4 * (wave * IPW + i) + l_row;          // row of the tile, 0..63
     k_chunk[i] = l_pos ^ (trow & 15);
     v_chunk[i] = l_pos ^ (4 * (trow & 3) + 2 * ((trow >> 2) & 1));
-    k_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + k_chunk[i] * 8;
-    v_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + v_chunk[i] * 8;
+    k_off[i] = static_cast<uint32_t>(((trow & 15) * p.stride_slot + k_chunk[i] * 8) * 2);
+    v_off[i] = static_cast<uint32_t>(((trow & 15) * p.stride_slot + v_chunk[i] * 8) * 2);
   }
   int k_rd[STEPS];
 #pragma unroll
@@ -994,30 +1017,54 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     s.id = sload1(row + min(s.kt * 4 + wave, last_blk));
     s.last_id = sload1(row + last_blk);
   };
-  auto issue = [&](const Slot& s, int stage) {
+  // A tile request is 8 DMA instructions per wave (4 for K, 4 for V), each moving 1 KiB.  The
+  // memory pipeline takes them at 64 bytes per clock, so issued back to back they hold the wave
+  // for hundreds of cycles: regular tiles are issued one instruction at a time between the MFMAs
+  // of the S phase instead (request_part), with a wave-uniform base in SGPRs and the lane's
+  // constant 32-bit offset.
+  const uint16_t *req_k = nullptr, *req_v = nullptr;
+  int req_stage = 0;
+  uint64_t req_mask = 0;                // all ones while a spread request is pending
+  auto request_part = [&](int part) {
+    const int i = part & 3, q = wave * IPW + i;
+    if (part < 4) dma16_s(k_off[i], req_k, &sK[req_stage][q * 512]);
+    else dma16_s(v_off[i], req_v, &sV[req_stage][q * 512]);
+  };
+  auto request_part_if = [&](int part) {
+    const int i = part & 3, q = wave * IPW + i;
+    if (part < 4) dma16_s_if(req_mask, k_off[i], req_k, &sK[req_stage][q * 512]);
+    else dma16_s_if(req_mask, v_off[i], req_v, &sV[req_stage][q * 512]);
+  };
+  auto prepare_regular = [&](const Slot& s, int stage) {
+    const int64_t at = static_cast<int64_t>(s.kvh) * p.stride_head + static_cast<int64_t>(s.id) * blk_stride;
+    req_k = kall + at;
+    req_v = vall + at;
+    req_stage = stage;
+  };
+  auto issue_frontier = [&](const Slot& s, int stage) {
+    // the tile that holds the frontier of its item (one per item, issued at once): rows past the
+    // frontier may be unallocated or hold anything, they fetch the frontier row instead (finite
+    // data, weight 0 after masking)
     const uint16_t* kg = kall + static_cast<int64_t>(s.kvh) * p.stride_head;
     const uint16_t* vg = vall + static_cast<int64_t>(s.kvh) * p.stride_head;
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int q = wave * IPW + i;
+      const int j_un = s.kt * kBN + 4 * q + l_row;
+      const bool over = j_un > s.wg_max;
+      const int j = over ? s.wg_max : j_un;
+      const int64_t slot = static_cast<int64_t>(over ? s.last_id : s.id) * CS_KV_BLOCK + j % CS_KV_BLOCK;
+      dma16(kg + slot * p.stride_slot + k_chunk[i] * 8, &sK[stage][q * 512]);
+      dma16(vg + slot * p.stride_slot + v_chunk[i] * 8, &sV[stage][q * 512]);
+    }
+  };
+  auto issue = [&](const Slot& s, int stage) {     // the whole request at once
     if (s.kt != s.wg_max / kBN) {
-      const int64_t base = static_cast<int64_t>(s.id) * blk_stride;
+      prepare_regular(s, stage);
 #pragma unroll
-      for (int i = 0; i < IPW; ++i) {
-        const int q = wave * IPW + i;
-        dma16(kg + base + k_off[i], &sK[stage][q * 512]);
-        dma16(vg + base + v_off[i], &sV[stage][q * 512]);
-      }
+      for (int part = 0; part < 2 * IPW; ++part) request_part(part);
     } else {
-      // the tile that holds the frontier: rows past it may be unallocated or hold anything, they
-      // fetch the frontier row instead (finite data, weight 0 after masking)
-#pragma unroll
-      for (int i = 0; i < IPW; ++i) {
-        const int q = wave * IPW + i;
-        const int j_un = s.kt * kBN + 4 * q + l_row;
-        const bool over = j_un > s.wg_max;
-        const int j = over ? s.wg_max : j_un;
-        const int64_t slot = static_cast<int64_t>(over ? s.last_id : s.id) * CS_KV_BLOCK + j % CS_KV_BLOCK;
-        dma16(kg + slot * p.stride_slot + k_chunk[i] * 8, &sK[stage][q * 512]);
-        dma16(vg + slot * p.stride_slot + v_chunk[i] * 8, &sV[stage][q * 512]);
-      }
+      issue_frontier(s, stage);
     }
   };
 
@@ -1078,6 +1125,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
       for (int kb = 0; kb < 2; ++kb)
         sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st % (KPF + 1)][kb], qf[st],
                                                            st == 0 ? zero16 : sacc[kb], 0, 0, 0);
+      request_part_if(st);
     }
     // pin that order (the scheduler would otherwise pull each read back to just before its use)
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * KPF, 0);
@@ -1209,7 +1257,25 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     for (int st = 0; st < STEPS; ++st) asm volatile("" : "+v"(qf[st]));
     asm volatile("" : "+v"(lim_raw));
     __syncthreads();                     // every wave's share landed; every wave left the other stage
-    if (nxt.live) issue(nxt, stage ^ 1);
+    if (new_item) {
+      lim = it_valid ? lim_raw : -1;
+      const int rows_here = min(32, it_rows_left);        // rows of this wave that exist
+      wave_min = rows_here > 0 ? __builtin_amdgcn_readlane(lim, 0) : -1;
+      wave_max = rows_here > 0 ? __builtin_amdgcn_readlane(lim, max(rows_here, 1) - 1) : -1;
+      new_item = false;
+    }
+    // request the next tile: at once if it holds the frontier of its item or if this wave has
+    // nothing to compute in this step, else spread over the S phase of this step
+    const bool computes = cur.kt * kBN <= wave_max;
+    req_mask = 0;
+    if (nxt.live) {
+      if (computes && nxt.kt != nxt.wg_max / kBN) {
+        prepare_regular(nxt, stage ^ 1);
+        req_mask = ~0ull;
+      } else {
+        issue(nxt, stage ^ 1);
+      }
+    }
 
     // scalar requests for later steps: block ids of the slot after next; at the last tile of an
     // item also the descriptor three items ahead
@@ -1224,14 +1290,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
       finish_item(ep_tok_head, ep_valid, ep_part);
       ep_pending = false;
     }
-    if (new_item) {
-      lim = it_valid ? lim_raw : -1;
-      const int rows_here = min(32, it_rows_left);        // rows of this wave that exist
-      wave_min = rows_here > 0 ? __builtin_amdgcn_readlane(lim, 0) : -1;
-      wave_max = rows_here > 0 ? __builtin_amdgcn_readlane(lim, max(rows_here, 1) - 1) : -1;
-      new_item = false;
-    }
-    if (cur.kt * kBN <= wave_max) compute(cur.kt, stage);
+    if (computes) compute(cur.kt, stage);
 
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nn.id), "+s"(nn.last_id), "+s"(d3));
     if (cur_last) {
@@ -1483,6 +1542,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         return CS_EINVAL;
       const AttnPlan a = plan_attn(n_q, n_streams, group, n_kv_heads, max_blocks);
       if (a.items_cap * kBM >= (1ll << 31)) return CS_EUNSUPPORTED;
+      if (stride_slot >= (1ll << 26)) return CS_EUNSUPPORTED;      // 32-bit byte offsets inside a cache block
       if (!workspace || workspace_bytes < a.total || !cs::aligned16(workspace)) return CS_EWORKSPACE;
       char* w = static_cast<char*>(workspace);
       p.bm = kBM;
