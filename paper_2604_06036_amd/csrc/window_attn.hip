@@ -4,7 +4,7 @@
 // causal attention reads a cache that mixes reused (position-corrected) states with states
 // written in the current pass.  Causality follows the window-sequence index of each query.
 //
-// bf16 kernel (matrix cores).  One workgroup = 4 waves = a tile of 128 "rows", a row being one
+// bf16 kernels (matrix cores).  A workgroup = 4 waves = a tile of 128 "rows", a row being one
 // (query token, query head of one kv group) pair, so the K/V tiles a workgroup stages in LDS are
 // shared by all query heads of the group.  Keys are swept in tiles of 64 through LDS:
 //   S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K fragment from LDS (ds_read_b128),
@@ -14,10 +14,14 @@
 //   O^T += V^T P^T   P^T is already in B-operand layout (no LDS round trip); the V^T fragment is
 //                    fetched from the row-major V tile with the LDS transpose read
 //                    (ds_read_b64_tr_b16), so V is never transposed in memory.
-// Global loads of the next K/V tile are issued before the current tile is computed.  Tiles that
-// lie wholly above a wave's causal frontier are skipped by that wave; only tiles that straddle a
-// frontier pay for masking.  Cache rows past the workgroup's frontier are never read (they may be
-// unallocated) and are staged as zeros so that 0 * garbage cannot produce NaN.
+// Tiles that lie wholly above a wave's causal frontier are skipped by that wave; only tiles that
+// straddle a frontier pay for masking.  Cache rows past the workgroup's frontier are never read
+// (they may be unallocated): the lanes that would fetch them fetch the frontier row instead.
+//
+// head_dim 128: a planning kernel lists the work items of the launch and persistent workgroups
+// stream K/V tiles from HBM straight into LDS (global_load_lds), across item boundaries; long key
+// sweeps of small batches are split over several items and merged by a second kernel.
+// head_dim 64: one workgroup per row tile, tiles staged through registers.
 //
 // fp32 kernel: plain SIMT, one wave per (query, head), keys strided over lanes, online softmax
 // per lane and a final cross-lane merge.  It exists for fp32 caches (small validation shapes).
@@ -46,9 +50,8 @@ struct AttnParams {
   int32_t max_blocks, n_streams, n_q_heads, n_kv_heads, group;
   float scale, scale_log2e;
   int64_t n_q;
-  int32_t xcd_chunk;     // > 0: workgroup b runs item (b % 8) * xcd_chunk + b / 8
   // split-KV (max_splits > 1): a row tile whose key sweep is longer than chunk_tiles key tiles is
-  // shared by several workgroups; their un-normalised partial results go to the workspace and a
+  // shared by several work items; their un-normalised partial results go to the workspace and a
   // second kernel merges them (merging in the last workgroup to finish was tried and is far
   // slower here: the device-scope release/acquire it needs writes back and invalidates the L2)
   int32_t chunk_tiles, max_splits, bm;
@@ -301,21 +304,17 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
 }
 
 // ------------------------------------------------------------------------------------------
-// Asynchronous-pipeline variant for head_dim 128 (the shape of every bf16 workload measured).
+// Tile transport for head_dim 128 (the shape of every bf16 workload measured).
 //
-// Same mathematics and register layouts as the kernel above; what changes is how K/V tiles reach
-// LDS.  Tiles are copied global -> LDS by the DMA form of the global load
+// K/V tiles are copied global -> LDS by the DMA form of the global load
 // (global_load_lds_dwordx4: lane l of a wave deposits its 16 bytes at base + 16 l, the source
-// address is free per lane), NS tiles deep, so nothing is staged through registers, there is one
-// workgroup barrier per tile instead of two, and a tile is requested NS-1 tiles before it is
-// used.  Because the DMA fixes the LDS position of each lane's chunk, bank conflicts are avoided
-// by choosing WHICH 16-byte chunk of a row each lane fetches (an XOR swizzle on the source side)
-// instead of padding rows:
-//   K tile row r: chunk c is stored at position c ^ (r % 16)       (ds_read_b128 of 16 rows at one c)
-//   V tile row r: chunk c is stored at position c ^ (2 (r % 8))    (transpose reads: 4 rows x 2 chunks)
-// NW = 8 waves (256 rows, one workgroup per CU, NS = 4) for large grids, NW = 4 (128 rows, two
-// workgroups per CU, NS = 2) otherwise.  Workgroups are numbered so that all row tiles of one
-// (stream, kv head) pair run on the same XCD (shared L2) when there are enough pairs to balance.
+// address is free per lane), so nothing is staged through registers and there is one workgroup
+// barrier per tile.  Because the DMA fixes the LDS position of each lane's chunk, bank conflicts
+// are avoided by choosing WHICH 16-byte chunk of a row each lane fetches (an XOR swizzle on the
+// source side) instead of padding rows:
+//   K tile row r: chunk c is stored at position c ^ (r % 16)   (ds_read_b128 of 16 rows at one c)
+//   V tile row r: chunk c is stored at position c ^ (4 (r % 4) + 2 ((r / 4) % 2))
+//                 (a transpose read touches 8 rows x 2 chunks: this spreads them over all banks)
 typedef __attribute__((address_space(3))) void lds_void_t;
 
 // One 16-byte-per-lane DMA copy global -> LDS (lane l lands at lds_addr + 16 l).  Issued as inline
@@ -361,340 +360,6 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <int NW, int NS>
-__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void window_attn_bf16_async_kernel(AttnParams p) {
-  constexpr int D = 128;
-  constexpr int BM = 32 * NW;           // rows per workgroup
-  constexpr int STEPS = D / 16, DB = D / 32;
-  constexpr int TILE = kBN * D;         // elements of one K (or V) tile: 16 KiB, unpadded
-  constexpr int IPW = 16 / NW;          // 1-KiB DMA instructions per wave, per tile, per tensor
-  constexpr int AHEAD = NS - 1;         // tiles requested ahead of the one being computed
-
-  __shared__ __attribute__((aligned(1024))) uint16_t sK[NS][TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t sV[NS][TILE];
-  extern __shared__ int32_t s_bt[];
-
-  // ---- work item: XCD-aware renumbering, then (stream, kv head, row tile).  Every wave finds
-  //      the stream by a 64-streams-at-a-time prefix sum over cu_q (a serial scan of cu_q costs
-  //      one dependent memory round trip per stream, microseconds for the last streams).
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n = lane & 31, h = lane >> 5;
-  int v = blockIdx.x;
-  if (p.xcd_chunk > 0) v = (v & 7) * p.xcd_chunk + (v >> 3);
-  const int split = v % p.max_splits;
-  v /= p.max_splits;
-  const int item = v;
-  int s = -1, q0 = 0, rows_total = 0, n_row_tiles = 0;
-  for (int s0 = 0; s0 < p.n_streams; s0 += 64) {
-    const int si = s0 + lane;
-    int c0 = 0, c1 = 0;
-    if (si < p.n_streams) {
-      c0 = p.cu_q[si];
-      c1 = p.cu_q[si + 1];
-    }
-    const int rows_i = (c1 - c0) * p.group;
-    const int tiles_i = (rows_i + BM - 1) / BM;
-    const int items_i = tiles_i * p.n_kv_heads;
-    int incl = items_i;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int t = __shfl_up(incl, off);
-      if (lane >= off) incl += t;
-    }
-    const int total = __builtin_amdgcn_readlane(incl, 63);
-    if (v < total) {
-      const int hit = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(__ballot(incl > v))) - 1);
-      s = s0 + hit;
-      q0 = __builtin_amdgcn_readlane(c0, hit);
-      rows_total = __builtin_amdgcn_readlane(rows_i, hit);
-      n_row_tiles = __builtin_amdgcn_readlane(tiles_i, hit);
-      v -= __builtin_amdgcn_readlane(incl, hit) - __builtin_amdgcn_readlane(items_i, hit);
-      break;
-    }
-    v -= total;
-  }
-  if (s < 0) {
-    if (p.max_splits > 1 && split == 0 && tid == 0) p.ws_desc[item * 8 + 4] = 0;   // nothing to merge
-    return;
-  }
-  const int kvh = v / n_row_tiles;
-  const int r_tile = (n_row_tiles - 1 - (v - kvh * n_row_tiles)) * BM;      // longest first
-
-  // the stream's block-table row goes to LDS; its length comes from kv_len so that these loads do
-  // not wait for the causal frontier (q_pos) to arrive
-  const int32_t* bt = p.block_table + static_cast<int64_t>(s) * p.max_blocks;
-  {
-    const int n_blk = min((p.kv_len[s] + CS_KV_BLOCK - 1) / CS_KV_BLOCK, p.max_blocks);
-    for (int i = tid; i < n_blk; i += NW * 64) s_bt[i] = bt[i];
-  }
-
-  const int row = r_tile + wave * 32 + n;
-  const bool valid = row < rows_total;
-  const int row_c = valid ? row : rows_total - 1;
-  const int tok = q0 + row_c / p.group;
-  const int head = kvh * p.group + row_c % p.group;
-  const int lim = valid ? p.q_pos[tok] : -1;
-
-  const int wg_last = min(r_tile + BM, rows_total) - 1;
-  const int wg_max = p.q_pos[q0 + wg_last / p.group];
-  const int w_first = r_tile + wave * 32;
-  const bool wave_live = w_first < rows_total;
-  const int w_last = min(w_first + 31, rows_total - 1);
-  const int wave_min = wave_live ? p.q_pos[q0 + w_first / p.group] : -1;
-  const int wave_max = wave_live ? p.q_pos[q0 + w_last / p.group] : -1;
-  const int n_key_tiles = wg_max / kBN + 1;
-  const int last_blk = wg_max / CS_KV_BLOCK;
-  const int n_split = (n_key_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
-  if (p.max_splits > 1 && split == 0 && tid == 0) {
-    int32_t* d = p.ws_desc + item * 8;
-    d[0] = q0; d[1] = rows_total; d[2] = r_tile; d[3] = kvh; d[4] = n_split;
-  }
-  if (split >= n_split) return;
-  const int kt_begin = split * p.chunk_tiles;
-  const int kt_end = min(n_key_tiles, kt_begin + p.chunk_tiles);
-
-  const uint16_t* qrow = static_cast<const uint16_t*>(p.q) +
-                         (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
-  bf16x8 qf[STEPS];
-#pragma unroll
-  for (int st = 0; st < STEPS; ++st)
-    qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(qrow + 16 * st + 8 * h));
-
-  f32x16 o[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m_run = kNegInf, l_run = 0.f;
-  const float slack = kMaxSlack / p.scale_log2e;
-
-  // ---- DMA sources.  Instruction i of this wave moves tile rows 4 q .. 4 q + 3, q = wave*IPW + i;
-  //      lane l lands at (row 4 q + l / 16, position l % 16) and fetches the chunk that belongs there.
-  const uint16_t* kglob = static_cast<const uint16_t*>(p.k) + static_cast<int64_t>(kvh) * p.stride_head;
-  const uint16_t* vglob = static_cast<const uint16_t*>(p.v) + static_cast<int64_t>(kvh) * p.stride_head;
-  const int64_t blk_stride = static_cast<int64_t>(CS_KV_BLOCK) * p.stride_slot;
-  const int l_row = lane >> 4, l_pos = lane & 15;
-  int64_t k_off[IPW], v_off[IPW];      // element offsets inside a cache block, constant per lane
-  int k_chunk[IPW], v_chunk[IPW];
-#pragma unroll
-  for (int i = 0; i < IPW; ++i) {
-    const int trow = 4 * (wave * IPW + i) + l_row;          // row of the tile, 0..63
-    k_chunk[i] = l_pos ^ (trow & 15);
-    v_chunk[i] = l_pos ^ (4 * (trow & 3) + 2 * ((trow >> 2) & 1));
-    k_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + k_chunk[i] * 8;
-    v_off[i] = static_cast<int64_t>(trow & 15) * p.stride_slot + v_chunk[i] * 8;
-  }
-
-  __syncthreads();                       // block-table row staged
-
-  // All DMA instructions of one wave for one tile read the same 16-slot cache block (instruction q
-  // covers tile rows 4 q .. 4 q + 3, i.e. block q / 4 of the tile's four): one table entry per wave
-  // and tile, read from LDS one tile ahead of its use so that its latency is never waited for.
-  const int bt_sub = (wave * IPW) / 4;
-  auto bt_entry = [&](int key_tile) {
-    return s_bt[min(key_tile * 4 + bt_sub, last_blk)];
-  };
-  int blk_next = 0;
-  auto issue = [&](int key_tile, int stage) {
-    const bool last = key_tile == n_key_tiles - 1;
-    if (!last) {
-      const int64_t base = static_cast<int64_t>(__builtin_amdgcn_readfirstlane(blk_next)) * blk_stride;
-#pragma unroll
-      for (int i = 0; i < IPW; ++i) {
-        const int q = wave * IPW + i;
-        dma16(kglob + base + k_off[i], &sK[stage][q * 512]);
-        dma16(vglob + base + v_off[i], &sV[stage][q * 512]);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < IPW; ++i) {
-        const int q = wave * IPW + i;
-        // rows past the frontier may be unallocated or hold anything: they fetch the frontier row
-        // instead (finite data, weight 0 after masking)
-        const int j = min(key_tile * kBN + 4 * q + l_row, wg_max);
-        const int64_t slot = static_cast<int64_t>(s_bt[j / CS_KV_BLOCK]) * CS_KV_BLOCK + j % CS_KV_BLOCK;
-        dma16(kglob + slot * p.stride_slot + k_chunk[i] * 8, &sK[stage][q * 512]);
-        dma16(vglob + slot * p.stride_slot + v_chunk[i] * 8, &sV[stage][q * 512]);
-      }
-    }
-    blk_next = bt_entry(key_tile + 1);
-  };
-
-  // ---- LDS read addresses (elements), constant per lane
-  int k_rd[STEPS];                      // K fragment of step st: row n of a 32-key block
-#pragma unroll
-  for (int st = 0; st < STEPS; ++st) k_rd[st] = n * D + (((2 * st + h) ^ (n & 15)) << 3);
-  const int i16 = lane & 15, gid = (lane >> 4) & 1;
-  const int v_row = 4 * h + (i16 >> 2);                       // 0..7: row inside an 8-key group
-  const int v_swz = 4 * (v_row & 3) + 2 * (v_row >> 2);
-  int v_rd[DB];                          // V transpose read of d-block db: row v_row of the group
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-    v_rd[db] = v_row * D + (((4 * db + 2 * gid + ((i16 & 3) >> 1)) ^ v_swz) << 3) + 4 * (i16 & 1);
-
-  auto compute = [&](int kt, int stage) {
-    const int j0 = kt * kBN;
-    const uint16_t* tK = sK[stage];
-    const uint16_t* tV = sV[stage];
-    f32x16 sacc[2];
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    // K fragments are read two steps ahead of the MFMAs that consume them
-    constexpr int KPF = 2;
-    bf16x8 ka[KPF + 1][2];
-    auto k_frag = [&](int st, int kb) {
-      return __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(&tK[kb * 32 * D + k_rd[st]]));
-    };
-#pragma unroll
-    for (int st = 0; st < KPF; ++st) {
-      ka[st][0] = k_frag(st, 0);
-      ka[st][1] = k_frag(st, 1);
-    }
-#pragma unroll
-    for (int st = 0; st < STEPS; ++st) {
-      if (st + KPF < STEPS) {
-        ka[(st + KPF) % (KPF + 1)][0] = k_frag(st + KPF, 0);
-        ka[(st + KPF) % (KPF + 1)][1] = k_frag(st + KPF, 1);
-      }
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st % (KPF + 1)][kb], qf[st],
-                                                           st == 0 ? zero16 : sacc[kb], 0, 0, 0);
-    }
-    // pin that order: 2 KPF reads up front, then two reads behind every two MFMAs (the scheduler
-    // would otherwise pull each read back to just before its use and expose the LDS latency)
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * KPF, 0);
-#pragma unroll
-    for (int st = 0; st < STEPS - KPF; ++st) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2 * KPF, 0);
-    if (j0 + kBN - 1 > wave_min) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = j0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
-          if (key > lim) sacc[kb][r] = kNegInf;
-        }
-    }
-    float t_max = kNegInf;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[kb][r]);
-    t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
-    if (__any(t_max > m_run + slack)) {
-      const bool up = t_max > m_run + slack;
-      const float m_new = up ? t_max : m_run;
-      const float alpha = up ? __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e) : 1.f;
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-    }
-    const float m_scaled = (m_run == kNegInf ? 0.f : m_run) * p.scale_log2e;
-    bf16x8 pb[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int mm = 0; mm < 2; ++mm) {
-        cs::u32x4 w;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
-          const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
-          const uint32_t pk = pack_bf16x2(e0, e1);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
-                                                  __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run, false);
-          w[c] = pk;
-        }
-        pb[kb][mm] = __builtin_bit_cast(bf16x8, w);
-      }
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int mm = 0; mm < 2; ++mm) {
-        const int g0 = (32 * kb + 16 * mm) * D;             // first 8-key group of this MFMA
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + v_rd[db]]));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + 8 * D + v_rd[db]]));
-          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kb][mm],
-                                                         o[db], 0, 0, 0);
-        }
-      }
-  };
-
-  // The Q fragments must be complete before the loop: a wait for them inside it would also
-  // drain the K/V requests in flight (vector-memory operations retire in order).
-#pragma unroll
-  for (int st = 0; st < STEPS; ++st) asm volatile("" : "+v"(qf[st]));
-
-  // ---- pipeline over this workgroup's key tiles [kt_begin, kt_end): the i-th of them lives in
-  //      stage i % NS and is requested AHEAD tiles early
-  const int n_my = kt_end - kt_begin;
-  blk_next = bt_entry(kt_begin);
-#pragma unroll
-  for (int t = 0; t < AHEAD; ++t)
-    if (t < n_my) issue(kt_begin + t, t);
-  for (int i0 = 0; i0 < n_my; i0 += NS) {
-#pragma unroll
-    for (int u = 0; u < NS; ++u) {
-      const int i = i0 + u;
-      if (i < n_my) {
-        const int kt = kt_begin + i;
-        // this wave's share of the tile has landed once at most the requests of later tiles remain
-        const int later = min(AHEAD - 1, n_my - 1 - i);
-        if (later >= 2) wait_vmcnt<2 * 2 * IPW>();
-        else if (later == 1) wait_vmcnt<1 * 2 * IPW>();
-        else wait_vmcnt<0>();
-        __syncthreads();                   // everyone's share landed; everyone left the previous tile
-        if (i + AHEAD < n_my) issue(kt + AHEAD, (u + AHEAD) % NS);
-        if (kt * kBN <= wave_max) compute(kt, u);
-      }
-    }
-  }
-
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (n_split > 1) {
-    // partial result of this key range: un-normalised rows, reference maximum and row sum
-    const int64_t prow = (static_cast<int64_t>(item) * p.max_splits + split) * BM + wave * 32 + n;
-    if (h == 0) {
-      p.ws_ml[prow * 2] = m_run;
-      p.ws_ml[prow * 2 + 1] = l_tot;
-    }
-    float* po = p.ws_o + prow * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const cs::u32x4 w = {__float_as_uint(o[db][4 * rq + 0]), __float_as_uint(o[db][4 * rq + 1]),
-                             __float_as_uint(o[db][4 * rq + 2]), __float_as_uint(o[db][4 * rq + 3])};
-        *reinterpret_cast<cs::u32x4*>(po + 32 * db + 8 * rq + 4 * h) = w;
-      }
-    return;
-  }
-  if (valid) {
-    const float inv = 1.f / l_tot;
-    uint16_t* orow = static_cast<uint16_t*>(p.out) +
-                     (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        cs::u32x2 w;
-        w.x = pack_bf16x2(o[db][4 * rq + 0] * inv, o[db][4 * rq + 1] * inv);
-        w.y = pack_bf16x2(o[db][4 * rq + 2] * inv, o[db][4 * rq + 3] * inv);
-        *reinterpret_cast<cs::u32x2*>(orow + 32 * db + 8 * rq + 4 * h) = w;
-      }
-  }
-}
-
 // =============================================================================================
 // bf16 / head_dim 128: planned, persistent kernel
 //
@@ -727,7 +392,7 @@ constexpr int kSortMax = 2048;        // streams sorted by work in LDS; beyond, 
 struct PlanParams {
   const int32_t* __restrict__ cu_q;
   const int32_t* __restrict__ q_pos;
-  int32_t n_streams, group, n_kv_heads, chunk_tiles, max_splits, max_tiles, r_cap;
+  int32_t n_streams, group, n_kv_heads, chunk_tiles, max_splits, max_tiles, r_cap, bm;
   int32_t* header;      // [kPlanHeaderInts]
   int32_t* items;       // [items_cap][8]
   int32_t* rt_desc;     // [r_cap * n_kv_heads][8]: q0, rows_total, r_tile, kvh, n_split
@@ -781,7 +446,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     int tiles = 0;
     if (s < pp.n_streams) {
       const int rows = (pp.cu_q[s + 1] - pp.cu_q[s]) * pp.group;
-      tiles = (rows + kBM - 1) / kBM;
+      tiles = (rows + pp.bm - 1) / pp.bm;
       pp.st_work[s] = 0;
     }
     int total;
@@ -805,7 +470,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     const int t = r - pp.st_toff[s];
     const int q0 = pp.cu_q[s];
     const int rows = (pp.cu_q[s + 1] - q0) * pp.group;
-    const int last_row = min((t + 1) * kBM, rows) - 1;
+    const int last_row = min((t + 1) * pp.bm, rows) - 1;
     const int wg_max = pp.q_pos[q0 + last_row / pp.group];
     pp.rt_stream[r] = s;
     pp.rt_wgmax[r] = wg_max;
@@ -908,16 +573,16 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     for (int kvh = 0; kvh < pp.n_kv_heads; ++kvh) {
       const int rt_id = r * pp.n_kv_heads + kvh;
       int32_t* rd = pp.rt_desc + static_cast<int64_t>(rt_id) * 8;
-      rd[0] = q0; rd[1] = rows; rd[2] = t * kBM; rd[3] = kvh; rd[4] = n_split;
+      rd[0] = q0; rd[1] = rows; rd[2] = t * pp.bm; rd[3] = kvh; rd[4] = n_split;
       for (int c = 0; c < n_split; ++c) {
         const int kb = n_split > 1 ? c * pp.chunk_tiles : 0;
         const int ke = n_split > 1 ? min(n_kt, kb + pp.chunk_tiles) : n_kt;
         const int x = xcd_of(r, s, kvh, c);
         const int pos = s_list_off[x] + atomicAdd(&pp.hist[x * hist_pitch + min(ke - kb, pp.max_tiles + 1)], 1);
         int32_t* it = pp.items + static_cast<int64_t>(pos) * 8;
-        it[0] = q0; it[1] = rows; it[2] = t * kBM; it[3] = kvh | (s << 8); it[4] = wg_max;
+        it[0] = q0; it[1] = rows; it[2] = t * pp.bm; it[3] = kvh | (s << 8); it[4] = wg_max;
         it[5] = kb; it[6] = ke;
-        it[7] = n_split > 1 ? (rt_id * pp.max_splits + c) * kBM : -1;
+        it[7] = n_split > 1 ? (rt_id * pp.max_splits + c) * pp.bm : -1;
       }
     }
   }
@@ -1179,20 +844,23 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
         }
         pb[kb][mm] = __builtin_bit_cast(bf16x8, w);
       }
+    // 16 MFMAs, m = (key block, key half, d block); V^T fragments are read VPF MFMAs ahead
+    constexpr int VPF = 3;
+    s16x4 vlo[VPF + 1], vhi[VPF + 1];
+    auto v_frag = [&](int m) {
+      const int g0 = (32 * (m >> 3) + 16 * ((m >> 2) & 1)) * D, db = m & 3;
+      vlo[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + v_rd[db]]));
+      vhi[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + 8 * D + v_rd[db]]));
+    };
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int m = 0; m < VPF; ++m) v_frag(m);
 #pragma unroll
-      for (int mm = 0; mm < 2; ++mm) {
-        const int g0 = (32 * kb + 16 * mm) * D;             // first 8-key group of this MFMA
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + v_rd[db]]));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + 8 * D + v_rd[db]]));
-          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[kb][mm],
-                                                         o[db], 0, 0, 0);
-        }
-      }
+    for (int m = 0; m < 16; ++m) {
+      if (m + VPF < 16) v_frag(m + VPF);
+      const s16x8 a = __builtin_shufflevector(vlo[m % (VPF + 1)], vhi[m % (VPF + 1)], 0, 1, 2, 3, 4, 5, 6, 7);
+      o[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[m >> 3][(m >> 2) & 1],
+                                                        o[m & 3], 0, 0, 0);
+    }
   };
 
   // Normalises and stores the rows of the finished item (or its un-normalised partial rows when
@@ -1430,13 +1098,15 @@ struct AttnPlan {
   int chunk_tiles;       // key tiles per item when a row tile's sweep is split
   int max_splits, max_tiles;
   int grid;              // persistent workgroups: 8 XCDs x up to 64
+  int bm;                // rows per item
   size_t off_items, off_rt_desc, off_st_toff, off_st_work, off_st_rank, off_rt_stream, off_rt_wgmax,
       off_hist, off_ml, off_o, total;
 };
 
 AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_heads, int32_t max_blocks) {
   AttnPlan a;
-  a.r_cap = (n_q * group) / kBM + n_streams;
+  a.bm = kBM;
+  a.r_cap = (n_q * group) / a.bm + n_streams;
   a.rt_cap = a.r_cap * n_kv_heads;
   a.max_tiles = static_cast<int>((static_cast<int64_t>(max_blocks) * CS_KV_BLOCK + kBN - 1) / kBN);
   // split long key sweeps when the row tiles alone cannot fill the chip a couple of times over
@@ -1468,8 +1138,8 @@ AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_h
   a.off_rt_wgmax = take(static_cast<size_t>(a.r_cap) * sizeof(int32_t));
   a.off_hist = take(static_cast<size_t>(8) * (a.max_tiles + 2) * sizeof(int32_t));
   const bool split = a.max_splits > 1;
-  a.off_ml = take(split ? static_cast<size_t>(a.items_cap) * kBM * 2 * sizeof(float) : 0);
-  a.off_o = take(split ? static_cast<size_t>(a.items_cap) * kBM * 128 * sizeof(float) : 0);
+  a.off_ml = take(split ? static_cast<size_t>(a.items_cap) * a.bm * 2 * sizeof(float) : 0);
+  a.off_o = take(split ? static_cast<size_t>(a.items_cap) * a.bm * 128 * sizeof(float) : 0);
   a.total = (at + 255) & ~static_cast<size_t>(255);
   return a;
 }
@@ -1532,7 +1202,6 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   p.scale = softmax_scale;
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   p.n_q = n_q;
-  p.xcd_chunk = 0;
   hipStream_t st = cs::as_stream(stream);
   if (dtype == CS_BF16) {
     const size_t bt_bytes = static_cast<size_t>(max_blocks) * sizeof(int32_t);
@@ -1541,11 +1210,11 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
       if (plan_mode != CS_ATTN_PLAN_BUILD && plan_mode != CS_ATTN_PLAN_REUSE && plan_mode != CS_ATTN_PLAN_ONLY)
         return CS_EINVAL;
       const AttnPlan a = plan_attn(n_q, n_streams, group, n_kv_heads, max_blocks);
-      if (a.items_cap * kBM >= (1ll << 31)) return CS_EUNSUPPORTED;
+      if (a.items_cap * a.bm >= (1ll << 31)) return CS_EUNSUPPORTED;
       if (stride_slot >= (1ll << 26)) return CS_EUNSUPPORTED;      // 32-bit byte offsets inside a cache block
       if (!workspace || workspace_bytes < a.total || !cs::aligned16(workspace)) return CS_EWORKSPACE;
       char* w = static_cast<char*>(workspace);
-      p.bm = kBM;
+      p.bm = a.bm;
       p.chunk_tiles = a.chunk_tiles;
       p.max_splits = a.max_splits;
       p.ws_plan = reinterpret_cast<const int32_t*>(w);
@@ -1564,6 +1233,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         pp.max_splits = a.max_splits;
         pp.max_tiles = a.max_tiles;
         pp.r_cap = static_cast<int32_t>(a.r_cap);
+        pp.bm = a.bm;
         pp.header = reinterpret_cast<int32_t*>(w);
         pp.items = reinterpret_cast<int32_t*>(w + a.off_items);
         pp.rt_desc = reinterpret_cast<int32_t*>(w + a.off_rt_desc);
@@ -1582,7 +1252,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
       if (a.max_splits > 1) {
         const int e = cs::note_hip(hipGetLastError());
         if (e != CS_OK) return e;
-        hipLaunchKernelGGL(window_attn_merge_kernel, dim3(static_cast<unsigned>(a.rt_cap * (kBM / 8))),
+        hipLaunchKernelGGL(window_attn_merge_kernel, dim3(static_cast<unsigned>(a.rt_cap * (a.bm / 8))),
                            dim3(256), 0, st, p);
       }
     } else {

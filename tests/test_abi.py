@@ -83,11 +83,12 @@ def test_host_side_argument_errors(lib):
     # (d)
     def attn(**kw):
         a = dict(q=one, k=one, v=one, cu=one, pos=one, kvl=one, bt=one, maxb=4, bs=16, out=one, nq=8,
-                 ns=1, hq=4, hkv=2, d=128, ss=256, sh=128, scale=0.1, dt=1)
+                 ns=1, hq=4, hkv=2, d=128, ss=256, sh=128, scale=0.1, dt=1, ws=z, wsb=0, mode=0)
         a.update(kw)
         return L.cs_window_prefill_attn(a["q"], a["k"], a["v"], a["cu"], a["pos"], a["kvl"], a["bt"],
                                         a["maxb"], a["bs"], a["out"], a["nq"], a["ns"], a["hq"], a["hkv"],
-                                        a["d"], a["ss"], a["sh"], a["scale"], a["dt"], z, 0, z)
+                                        a["d"], a["ss"], a["sh"], a["scale"], a["dt"], a["ws"], a["wsb"],
+                                        a["mode"], z)
     assert attn(q=z) == binding.CS_EINVAL
     assert attn(hq=5) == binding.CS_EINVAL
     assert attn(d=96) == binding.CS_EUNSUPPORTED
@@ -97,6 +98,13 @@ def test_host_side_argument_errors(lib):
     assert attn(ss=257) == binding.CS_EUNSUPPORTED
     assert attn(nq=0) == binding.CS_OK
     assert attn(nq=-2) == binding.CS_EINVAL
+    # bf16 / head_dim 128 keeps its work plan in the workspace: none, too small, unknown plan mode
+    need = L.cs_window_prefill_attn_workspace(8, 1, 4, 2, 128, 4, 1)
+    assert need > 0
+    assert attn() == binding.CS_EWORKSPACE
+    assert attn(ws=one, wsb=need - 1) == binding.CS_EWORKSPACE
+    assert attn(ws=one, wsb=need, mode=7) == binding.CS_EINVAL
+    assert attn(hkv=4, hq=4, ns=1 << 23, ws=one, wsb=1 << 40) == binding.CS_EUNSUPPORTED
 
 
 def test_product_package_does_not_import_the_oracle():

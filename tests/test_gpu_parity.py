@@ -319,6 +319,8 @@ ATTN_CASES = [
     ("bf16", 28, 4, 128, [64, 65, 127, 128], [5, 9, 19, 37]),  # frontiers on tile edges
     ("bf16", 28, 4, 128, [6033], [300]),                      # long sweep, few rows: split over keys
     ("bf16", 8, 2, 128, [3000, 700, 40], [257, 64, 40]),      # split and unsplit row tiles in one launch
+    ("bf16", 2, 1, 128, [20] * 2100, [2] * 2100),             # more streams than the planner sorts
+    ("bf16", 28, 4, 128, [300 + 7 * i for i in range(40)], [60 + i for i in range(40)]),   # > 512 work items
 ]
 
 
@@ -328,6 +330,57 @@ def test_window_prefill_attn(cs, case):
     say(f"window_prefill_attn case {case}: {dtype} heads={hq}/{hkv} d={d} kv={kv_lens} n_q={n_qs}")
     stats = _attn_case(cs, np.random.default_rng(3000 + case), dtype, hq, hkv, d, kv_lens, n_qs)
     say(f"  -> {stats}")
+
+
+def test_attention_plan_modes(cs):
+    """The work plan depends on cu_q / q_pos only: built by one call (or by a plan-only call), it
+    serves later calls on other Q / K / V (the decoder layers of a step) in REUSE mode."""
+    say("window_prefill_attn: plan built once, reused for other layers; plan-only call")
+    rng = np.random.default_rng(41)
+    hq, hkv, d = 28, 4, 128
+    kv_lens = [700, 90, 1300, 260, 33]
+    n_qs = [120, 90, 300, 7, 20]
+    n_streams = len(kv_lens)
+    nb = [(-(-L // 16)) for L in kv_lens]
+    max_blocks = max(nb)
+    ids = rng.permutation(sum(nb))
+    bt = np.zeros((n_streams, max_blocks), np.int32)
+    at = 0
+    for s in range(n_streams):
+        bt[s, : nb[s]] = ids[at: at + nb[s]]
+        at += nb[s]
+    q_pos = np.concatenate([np.sort(rng.choice(kv_lens[s], n_qs[s], replace=False)) for s in range(n_streams)]).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(n_qs)]).astype(np.int32)
+    n_q = int(q_pos.size)
+    scale = 1.0 / math.sqrt(d)
+    layers = []
+    for _ in range(3):
+        q = _pool(rng, (n_q, hq, d), "bf16")
+        kc = _pool(rng, (sum(nb) * 16, hkv, d), "bf16")
+        vc = _pool(rng, (sum(nb) * 16, hkv, d), "bf16")
+        layers.append((q, kc, vc, oc.window_attn(hp.f64(q), hp.f64(kc), hp.f64(vc), cu, q_pos, bt, hq, scale)))
+    wsb = cs.cs_window_prefill_attn_workspace(n_q, n_streams, hq, hkv, d, max_blocks, cs.CS_BF16)
+    meta = (torch.from_numpy(cu).to(DEV), torch.from_numpy(q_pos).to(DEV),
+            torch.tensor(kv_lens, dtype=torch.int32, device=DEV), torch.from_numpy(bt).to(DEV))
+
+    def run(layer, ws, mode):
+        q, kc, vc, ref = layers[layer]
+        out = torch.full((n_q, hq, d), 7.0, dtype=torch.bfloat16, device=DEV)
+        kd, vd = kc.to(DEV), vc.to(DEV)
+        cs.cs_window_prefill_attn(q.to(DEV), kd, vd, *meta, max_blocks, 16, out, n_q, n_streams, hq, hkv, d,
+                                  kd.stride(0), kd.stride(1), scale, cs.CS_BF16, ws, wsb, mode)
+        torch.cuda.synchronize()
+        return hp.check_attention(out.cpu(), ref, "bf16")
+
+    ws = torch.randint(0, 255, (wsb,), dtype=torch.uint8, device=DEV)
+    run(0, ws, cs.CS_ATTN_PLAN_BUILD)
+    run(1, ws, cs.CS_ATTN_PLAN_REUSE)
+    run(2, ws, cs.CS_ATTN_PLAN_REUSE)
+    run(0, ws, cs.CS_ATTN_PLAN_REUSE)
+    ws2 = torch.randint(0, 255, (wsb,), dtype=torch.uint8, device=DEV)
+    cs.cs_window_prefill_attn(None, None, None, *meta, max_blocks, 16, None, n_q, n_streams, hq, hkv, d,
+                              hkv * d, d, scale, cs.CS_BF16, ws2, wsb, cs.CS_ATTN_PLAN_ONLY)
+    run(2, ws2, cs.CS_ATTN_PLAN_REUSE)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
