@@ -266,7 +266,9 @@ def main():
             traffic, traffic_detail = None, None
     if dominant == "cs_window_prefill_attn":
         ach = kernels[dominant]["TFLOPs"]
-        roofline = dict(bound="mfma", kernel="window_attn_bf16_kernel" if w.dtype == "bf16" else "window_attn_f32_kernel",
+        roofline = dict(bound="mfma", kernel=("window_attn_bf16_stream_kernel (+ window_attn_merge_kernel where the key sweep is split)"
+                                if w.dtype == "bf16" and w.head_dim == 128 else
+                                "window_attn_bf16_kernel" if w.dtype == "bf16" else "window_attn_f32_kernel"),
                         achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS,
                         traffic=traffic, traffic_detail=traffic_detail, algorithmic_bytes=work["d_bytes"],
                         flops_per_launch=work["d_flops"], ms_per_launch=t_d)

@@ -27,6 +27,8 @@
 // per lane and a final cross-lane merge.  It exists for fp32 caches (small validation shapes).
 #include <math.h>
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -55,7 +57,7 @@ struct AttnParams {
   // second kernel merges them (merging in the last workgroup to finish was tried and is far
   // slower here: the device-scope release/acquire it needs writes back and invalidates the L2)
   int32_t chunk_tiles, max_splits, bm;
-  const int32_t* ws_plan;   // plan header (list offsets per XCD, row-tile count, end item)
+  const int32_t* ws_plan;   // plan header (list offsets per XCD, row-tile count, end item, first items)
   const int32_t* ws_items;  // item descriptors, 8 ints each, the 8 XCD lists back to back
   int32_t* ws_desc;      // [items][8]: q0, rows_total, r_tile, kvh, n_split
   float* ws_ml;          // [items][max_splits][bm][2]: running max (raw score units), row sum
@@ -383,16 +385,22 @@ typedef __attribute__((ext_vector_type(8))) int32_t i32x8;
 
 // Item descriptor: 8 ints.  [0] first query token of the stream, [1] rows of the stream (tokens x
 // heads per kv group), [2] first row of the tile, [3] kv head | stream << 8, [4] highest visible
-// cache index among the tile's rows, [5],[6] key tiles [begin, end), [7] first row of the item's
-// partial result in the workspace, or -1 when the item covers the whole sweep and writes `out`.
-constexpr int kPlanHeaderInts = 32;   // [0..8] list offsets per XCD, [9] row tiles, [16..23] end item
+// cache index among the tile's rows, [5] key tiles [begin, end) as begin | end << 16, [6] index of
+// the item the same workgroup takes next (-1: none), [7] first row of the item's partial result in
+// the workspace, or -1 when the item covers the whole sweep and writes `out`.
+// Plan header (ints): [0..8] list offsets per XCD, [9] row tiles, [16..23] end item,
+// [32 + 4 (64 x + j) + k] k-th item (k = 0, 1, 2) of workgroup j of XCD x (-1: none).
+constexpr int kSlotsPerXcd = 64;      // persistent workgroups per XCD: 32 CUs x 2
+constexpr int kHdrEndItem = 16, kHdrHeads = 32;
+constexpr int kPlanHeaderInts = kHdrHeads + 4 * 8 * kSlotsPerXcd;
+constexpr int kItemFixedCostHalves = 3;  // per-item overhead in half key tiles, for the planner's balance
 constexpr int kPlanThreads = 1024;
 constexpr int kSortMax = 2048;        // streams sorted by work in LDS; beyond, stream order is kept
 
 struct PlanParams {
   const int32_t* __restrict__ cu_q;
   const int32_t* __restrict__ q_pos;
-  int32_t n_streams, group, n_kv_heads, chunk_tiles, max_splits, max_tiles, r_cap, bm;
+  int32_t n_streams, group, n_kv_heads, chunk_tiles, max_splits, max_tiles, r_cap, bm, n_slots, hist_pitch;   // n_slots: workgroups per XCD
   int32_t* header;      // [kPlanHeaderInts]
   int32_t* items;       // [items_cap][8]
   int32_t* rt_desc;     // [r_cap * n_kv_heads][8]: q0, rows_total, r_tile, kvh, n_split
@@ -401,7 +409,7 @@ struct PlanParams {
   int32_t* st_rank;     // [n_streams] rank by decreasing work
   int32_t* rt_stream;   // [r_cap]
   int32_t* rt_wgmax;    // [r_cap]
-  int32_t* hist;        // [8][max_tiles + 2] items per (XCD, length), then list cursors
+  int32_t* hist;        // [8][hist_pitch] items per (XCD, bucket), then list cursors
 };
 
 // Exclusive prefix sum over the kPlanThreads threads of the planning workgroup.
@@ -426,6 +434,23 @@ __device__ __forceinline__ int plan_block_scan(int v, int* s_wave, int& total) {
   return base + incl - v;
 }
 
+// Minimum of an unsigned value over the 64 lanes of a wave by DPP row shifts and row broadcasts
+// (a chain of six ds_bpermute shuffles costs several hundred cycles; this costs a few dozen).
+__device__ __forceinline__ uint32_t plan_wave_umin(uint32_t v) {
+  auto step = [&](auto ctrl, auto row_mask) {
+    const uint32_t t = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+        static_cast<int>(0xffffffffu), static_cast<int>(v), decltype(ctrl)::value, decltype(row_mask)::value, 0xf, false));
+    v = t < v ? t : v;
+  };
+  step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xf>{});   // row_shr:1
+  step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xf>{});   // row_shr:2
+  step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xf>{});   // row_shr:4
+  step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xf>{});   // row_shr:8
+  step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast:15
+  step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast:31
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
+}
+
 __device__ __forceinline__ int plan_xcd_of_pair(int pair) {
   const int round = pair >> 3, pos = pair & 7;
   return (round & 1) ? 7 - pos : pos;
@@ -436,7 +461,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   __shared__ unsigned long long s_key[kSortMax];
   __shared__ int s_list_off[9];
   const int tid = threadIdx.x;
-  const int hist_pitch = pp.max_tiles + 2;
+  const int hist_pitch = pp.hist_pitch;
 
   // ---- clear counters; row tiles per stream
   for (int i = tid; i < 8 * hist_pitch; i += kPlanThreads) pp.hist[i] = 0;
@@ -508,11 +533,21 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   __threadfence_block();
   __syncthreads();
 
-  // ---- items per (XCD, length)
+  // ---- order of an XCD's list.  With enough (stream, kv head) pairs to give every XCD two, a pair
+  //      goes to one XCD whole (boustrophedon deal by rank) and its row tiles stay together in the
+  //      list, pairs by rank, longest row tile first: the workgroups of an XCD then sweep the K/V
+  //      of few pairs at a time and share them in its L2 (an order by length alone re-read K/V
+  //      2.5 times from HBM).  Otherwise items are dealt round robin and ordered by length.
+  //      bucket = position class in the list (counting sort), XCD chosen alongside.
   const bool grouped = pp.n_streams * pp.n_kv_heads >= 16;
-  auto xcd_of = [&](int r, int s, int kvh, int split) {
-    return grouped ? plan_xcd_of_pair(pp.st_rank[s] * pp.n_kv_heads + kvh)
-                   : (r * pp.n_kv_heads + kvh + split) & 7;
+  auto place = [&](int r, int s, int kvh, int split, int len, int& bucket) {
+    if (grouped) {
+      const int pair = pp.st_rank[s] * pp.n_kv_heads + kvh;
+      bucket = pair >> 3;
+      return plan_xcd_of_pair(pair);
+    }
+    bucket = pp.max_tiles + 1 - min(len, pp.max_tiles + 1);
+    return (r * pp.n_kv_heads + kvh + split) & 7;
   };
   for (int r = tid; r < n_rt; r += kPlanThreads) {
     const int s = pp.rt_stream[r];
@@ -521,28 +556,30 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     for (int kvh = 0; kvh < pp.n_kv_heads; ++kvh)
       for (int c = 0; c < n_split; ++c) {
         const int len = n_split > 1 ? min(pp.chunk_tiles, n_kt - c * pp.chunk_tiles) : n_kt;
-        atomicAdd(&pp.hist[xcd_of(r, s, kvh, c) * hist_pitch + min(len, pp.max_tiles + 1)], 1);
+        int bucket;
+        const int x = place(r, s, kvh, c, len, bucket);
+        atomicAdd(&pp.hist[x * hist_pitch + bucket], 1);
       }
   }
   __threadfence_block();
   __syncthreads();
 
-  // ---- per XCD (one wave each): first list position of every length, longest first
+  // ---- per XCD (one wave each): first list position of every bucket
   {
     const int w = tid >> 6, lane = tid & 63;
     if (w < 8) {
       int* hx = pp.hist + w * hist_pitch;
       int run = 0;
-      for (int top = hist_pitch - 1; top >= 0; top -= 64) {
-        const int k = top - lane;                      // lane 0 takes the longest length
-        const int v = k >= 0 ? __hip_atomic_load(&hx[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+      for (int k0 = 0; k0 < hist_pitch; k0 += 64) {
+        const int k = k0 + lane;
+        const int v = k < hist_pitch ? __hip_atomic_load(&hx[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
         int incl = v;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
           const int t = __shfl_up(incl, off);
           if (lane >= off) incl += t;
         }
-        if (k >= 0) hx[k] = run + incl - v;
+        if (k < hist_pitch) hx[k] = run + incl - v;
         run += __shfl(incl, 63);
       }
       if (lane == 0) s_list_off[w + 1] = run;          // list length for now
@@ -554,9 +591,10 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     for (int x = 0; x < 8; ++x) s_list_off[x + 1] += s_list_off[x];
     for (int x = 0; x < 9; ++x) pp.header[x] = s_list_off[x];
     pp.header[9] = n_rt * pp.n_kv_heads;
-    for (int i = 10; i < kPlanHeaderInts; ++i) pp.header[i] = 0;
-    pp.header[16 + 4] = -1;                             // end item: no key tiles, nothing visible
-    pp.header[16 + 7] = -1;
+    for (int i = 10; i < kHdrHeads; ++i) pp.header[i] = 0;
+    pp.header[kHdrEndItem + 4] = -1;                    // end item: no key tiles, nothing visible
+    pp.header[kHdrEndItem + 6] = -1;
+    pp.header[kHdrEndItem + 7] = -1;
   }
   __threadfence_block();
   __syncthreads();
@@ -567,6 +605,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     const int t = r - pp.st_toff[s];
     const int q0 = pp.cu_q[s];
     const int rows = (pp.cu_q[s + 1] - q0) * pp.group;
+    const int tiles_s = (rows + pp.bm - 1) / pp.bm;
     const int wg_max = pp.rt_wgmax[r];
     const int n_kt = wg_max / kBN + 1;
     const int n_split = pp.max_splits > 1 ? min((n_kt + pp.chunk_tiles - 1) / pp.chunk_tiles, pp.max_splits) : 1;
@@ -577,12 +616,62 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
       for (int c = 0; c < n_split; ++c) {
         const int kb = n_split > 1 ? c * pp.chunk_tiles : 0;
         const int ke = n_split > 1 ? min(n_kt, kb + pp.chunk_tiles) : n_kt;
-        const int x = xcd_of(r, s, kvh, c);
-        const int pos = s_list_off[x] + atomicAdd(&pp.hist[x * hist_pitch + min(ke - kb, pp.max_tiles + 1)], 1);
+        int bucket;
+        const int x = place(r, s, kvh, c, ke - kb, bucket);
+        int* cursor = &pp.hist[x * hist_pitch + bucket];
+        // a pair's bucket holds its row tiles only: the longest (last) row tile goes first; where
+        // sweeps are split or buckets are shared, arrival order decides
+        const int within = grouped && pp.max_splits == 1 ? tiles_s - 1 - t : atomicAdd(cursor, 1);
+        const int start = grouped && pp.max_splits == 1 ? __hip_atomic_load(cursor, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+        const int pos = s_list_off[x] + start + within;
         int32_t* it = pp.items + static_cast<int64_t>(pos) * 8;
         it[0] = q0; it[1] = rows; it[2] = t * pp.bm; it[3] = kvh | (s << 8); it[4] = wg_max;
-        it[5] = kb; it[6] = ke;
+        it[5] = kb | (ke << 16); it[6] = -1;
         it[7] = n_split > 1 ? (rt_id * pp.max_splits + c) * pp.bm : -1;
+      }
+    }
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  // ---- deal every XCD's list to its workgroups (one wave per XCD, a lane per workgroup): items
+  //      in list order, each to the workgroup with the least work so far -- the schedule a run-time
+  //      queue would produce, fixed here so that the attention kernel needs no atomics.  Items of
+  //      one workgroup are chained through their `next` field.
+  {
+    const int w = tid >> 6, lane = tid & 63;
+    if (w < 8) {
+      const int begin = s_list_off[w], end = s_list_off[w + 1];
+      // work so far in half key tiles, with the lane number below it: the minimum names the winner
+      uint32_t load = lane < pp.n_slots ? static_cast<uint32_t>(lane) : 0xffffffffu;
+      int last = -1, first3[3] = {-1, -1, -1}, taken = 0;
+      for (int base = begin; base < end; base += 64) {
+        const int mine = base + lane;
+        int len = 0;
+        if (mine < end) {
+          const int kbe = __hip_atomic_load(&pp.items[static_cast<int64_t>(mine) * 8 + 5], __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+          len = (kbe >> 16) - (kbe & 0xffff);
+        }
+        const int n_here = min(64, end - base);
+        for (int k = 0; k < n_here; ++k) {
+          const uint32_t cost = static_cast<uint32_t>(2 * __builtin_amdgcn_readlane(len, k) + kItemFixedCostHalves) << 6;
+          const int winner = static_cast<int>(plan_wave_umin(load) & 63u);
+          if (lane == winner) {
+            const int idx = base + k;
+            if (last >= 0) pp.items[static_cast<int64_t>(last) * 8 + 6] = idx;
+            if (taken == 0) first3[0] = idx;
+            if (taken == 1) first3[1] = idx;
+            if (taken == 2) first3[2] = idx;
+            ++taken;
+            last = idx;
+            load += cost;
+          }
+        }
+      }
+      if (lane < kSlotsPerXcd) {
+        int32_t* hd = pp.header + kHdrHeads + 4 * (w * kSlotsPerXcd + lane);
+        hd[0] = first3[0]; hd[1] = first3[1]; hd[2] = first3[2]; hd[3] = taken;
       }
     }
   }
@@ -614,17 +703,16 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
 
-  // ---- this workgroup's items: positions j, 2S-1-j, 2S+j, ... of its XCD's list
-  const int xcd = blockIdx.x & 7, slot_j = blockIdx.x >> 3, n_slots = gridDim.x >> 3;
-  const int list_begin = p.ws_plan[xcd];
-  const int list_len = p.ws_plan[xcd + 1] - list_begin;
-  auto desc_ptr = [&](int i) -> const int32_t* {
-    const int idx = i * n_slots + ((i & 1) ? n_slots - 1 - slot_j : slot_j);
-    return idx < list_len ? p.ws_items + static_cast<int64_t>(list_begin + idx) * 8 : p.ws_plan + 16;
+  // ---- this workgroup's items: a chain through the `next` field of the descriptors, dealt by the
+  //      planning kernel; three descriptors of look-ahead are kept loaded
+  const int xcd = blockIdx.x & 7, slot_j = blockIdx.x >> 3;
+  auto item_at = [&](int idx) -> const int32_t* {
+    return idx >= 0 ? p.ws_items + static_cast<int64_t>(idx) * 8 : p.ws_plan + kHdrEndItem;
   };
-  i32x8 d0 = sload8(desc_ptr(0)), d1 = sload8(desc_ptr(1)), d2 = sload8(desc_ptr(2));
+  const int32_t* heads = p.ws_plan + kHdrHeads + 4 * (xcd * kSlotsPerXcd + slot_j);
+  i32x8 d0 = sload8(item_at(heads[0])), d1 = sload8(item_at(heads[1])), d2 = sload8(item_at(heads[2]));
   asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d0), "+s"(d1), "+s"(d2));
-  if (d0[6] == 0) return;               // the list is shorter than the grid
+  if ((d0[5] >> 16) == 0) return;       // nothing for this workgroup
   int seq0 = 0;                         // d0 is the seq0-th item of this workgroup
 
   // ---- constants of the lane: DMA sources inside a cache block, LDS read addresses
@@ -662,9 +750,9 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
   };
   auto first_slot = [&](const i32x8& d, int seq) {
     Slot s;
-    s.kt = d[5]; s.ke = d[6]; s.kvh = d[3] & 255; s.stream = d[3] >> 8; s.wg_max = d[4]; s.seq = seq;
+    s.kt = d[5] & 0xffff; s.ke = d[5] >> 16; s.kvh = d[3] & 255; s.stream = d[3] >> 8; s.wg_max = d[4]; s.seq = seq;
     s.id = 0; s.last_id = 0;
-    s.live = d[6] > 0 ? 1 : 0;
+    s.live = (d[5] >> 16) > 0 ? 1 : 0;
     return s;
   };
   auto successor = [&](const Slot& c) {
@@ -952,7 +1040,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     // request would let the compiler merge the pending register with another value before the wait)
     Slot nn = nxt.live ? successor(nxt) : nxt;
     request_ids(nn);
-    i32x8 d3 = sload8(cur_last ? desc_ptr(seq0 + 3) : p.ws_plan + 16);
+    i32x8 d3 = sload8(cur_last ? item_at(d2[6]) : p.ws_plan + kHdrEndItem);
 
     if (ep_pending) {
       finish_item(ep_tok_head, ep_valid, ep_part);
@@ -966,7 +1054,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
       ep_tok_head = it_tok_head;
       ep_valid = it_valid;
       ep_part = it_part;
-      if (d1[6] > 0) {
+      if ((d1[5] >> 16) > 0) {
         load_item(d1);
         new_item = true;
       }
@@ -1099,6 +1187,7 @@ struct AttnPlan {
   int max_splits, max_tiles;
   int grid;              // persistent workgroups: 8 XCDs x up to 64
   int bm;                // rows per item
+  int hist_pitch;        // buckets of the planner's counting sort, per XCD
   size_t off_items, off_rt_desc, off_st_toff, off_st_work, off_st_rank, off_rt_stream, off_rt_wgmax,
       off_hist, off_ml, off_o, total;
 };
@@ -1136,7 +1225,9 @@ AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_h
   a.off_st_rank = take(static_cast<size_t>(n_streams) * sizeof(int32_t));
   a.off_rt_stream = take(static_cast<size_t>(a.r_cap) * sizeof(int32_t));
   a.off_rt_wgmax = take(static_cast<size_t>(a.r_cap) * sizeof(int32_t));
-  a.off_hist = take(static_cast<size_t>(8) * (a.max_tiles + 2) * sizeof(int32_t));
+  const int64_t pair_rounds = (static_cast<int64_t>(n_streams) * n_kv_heads + 7) / 8;
+  a.hist_pitch = static_cast<int>((a.max_tiles + 2 > pair_rounds ? a.max_tiles + 2 : pair_rounds) + 1);
+  a.off_hist = take(static_cast<size_t>(8) * a.hist_pitch * sizeof(int32_t));
   const bool split = a.max_splits > 1;
   a.off_ml = take(split ? static_cast<size_t>(a.items_cap) * a.bm * 2 * sizeof(float) : 0);
   a.off_o = take(split ? static_cast<size_t>(a.items_cap) * a.bm * 128 * sizeof(float) : 0);
@@ -1211,7 +1302,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         return CS_EINVAL;
       const AttnPlan a = plan_attn(n_q, n_streams, group, n_kv_heads, max_blocks);
       if (a.items_cap * a.bm >= (1ll << 31)) return CS_EUNSUPPORTED;
-      if (stride_slot >= (1ll << 26)) return CS_EUNSUPPORTED;      // 32-bit byte offsets inside a cache block
+      if (stride_slot >= (1ll << 26) || a.max_tiles >= (1 << 15)) return CS_EUNSUPPORTED;      // 32-bit byte offsets inside a cache block
       if (!workspace || workspace_bytes < a.total || !cs::aligned16(workspace)) return CS_EWORKSPACE;
       char* w = static_cast<char*>(workspace);
       p.bm = a.bm;
@@ -1234,6 +1325,8 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         pp.max_tiles = a.max_tiles;
         pp.r_cap = static_cast<int32_t>(a.r_cap);
         pp.bm = a.bm;
+        pp.n_slots = a.grid / 8;
+        pp.hist_pitch = a.hist_pitch;
         pp.header = reinterpret_cast<int32_t*>(w);
         pp.items = reinterpret_cast<int32_t*>(w + a.off_items);
         pp.rt_desc = reinterpret_cast<int32_t*>(w + a.off_rt_desc);
