@@ -259,9 +259,14 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic_detail = json.load(open(tpath)).get(w.name, {}).get(dominant)
+            per_wl = json.load(open(tpath)).get(w.name, {})
+            traffic_detail = per_wl.get(dominant)
             if traffic_detail:
                 traffic = traffic_detail["read_bytes"] + traffic_detail["write_bytes"]
+                merge = per_wl.get("attn_merge") if dominant == "cs_window_prefill_attn" else None
+                if merge:                                    # split sweeps: the call is two kernels
+                    traffic += merge["read_bytes"] + merge["write_bytes"]
+                    traffic_detail = dict(traffic_detail, merge_kernel=merge)
         except Exception:
             traffic, traffic_detail = None, None
     if dominant == "cs_window_prefill_attn":
