@@ -690,7 +690,14 @@ __device__ __forceinline__ int32_t sload1(const void* ptr) {
   return v;
 }
 
-__global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnParams p) {
+// RB = 32-row blocks per wave.  RB = 1 is what runs: 128-row items, two workgroups per CU (two
+// waves per SIMD hide each other's latencies).  RB = 2 (256-row items, one workgroup per CU with
+// the whole register file, every K and V fragment read from LDS feeding two MFMAs) passes the same
+// tests but measured 15-25 % slower as it stands: with one wave per SIMD nothing hides the softmax
+// arithmetic unless the loop is software-pipelined by hand, and half the scores land in AGPRs.
+template <int RB>
+__global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_kernel(AttnParams p) {
+  constexpr int WROWS = 32 * RB;        // rows per wave
   constexpr int D = 128;
   constexpr int STEPS = D / 16, DB = D / 32;
   constexpr int TILE = kBN * D;         // elements of one K (or V) tile: 16 KiB, unpadded
@@ -744,13 +751,17 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
   // ---- a slot of the tile stream: one key tile of one item, with the cache-block ids its
   //      request needs (this wave's quarter of the tile, and the block of the item's frontier)
   struct Slot {
-    int kt, ke, kvh, stream, wg_max, seq;
+    int kt, ke, kvh, wg_max, seq;
+    const int32_t* row;  // the stream's block-table row
+    int64_t head_off;    // element offset of the kv head inside a cache row
     int id, last_id;
     int live;            // an int: a bool would leave tail padding that struct copies drag through memory
   };
   auto first_slot = [&](const i32x8& d, int seq) {
     Slot s;
-    s.kt = d[5] & 0xffff; s.ke = d[5] >> 16; s.kvh = d[3] & 255; s.stream = d[3] >> 8; s.wg_max = d[4]; s.seq = seq;
+    s.kt = d[5] & 0xffff; s.ke = d[5] >> 16; s.kvh = d[3] & 255; s.wg_max = d[4]; s.seq = seq;
+    s.row = p.block_table + static_cast<int64_t>(d[3] >> 8) * p.max_blocks;
+    s.head_off = static_cast<int64_t>(d[3] & 255) * p.stride_head;
     s.id = 0; s.last_id = 0;
     s.live = (d[5] >> 16) > 0 ? 1 : 0;
     return s;
@@ -765,10 +776,9 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     return first_slot(rel == 1 ? d1 : d2, c.seq + 1);
   };
   auto request_ids = [&](Slot& s) {
-    const int32_t* row = p.block_table + static_cast<int64_t>(s.stream) * p.max_blocks;
-    const int last_blk = max(s.wg_max, 0) / CS_KV_BLOCK;
-    s.id = sload1(row + min(s.kt * 4 + wave, last_blk));
-    s.last_id = sload1(row + last_blk);
+    const int last_blk = max(s.wg_max, 0) >> 4;           // CS_KV_BLOCK = 16
+    s.id = sload1(s.row + min(s.kt * 4 + wave, last_blk));
+    s.last_id = sload1(s.row + last_blk);
   };
   // A tile request is 8 DMA instructions per wave (4 for K, 4 for V), each moving 1 KiB.  The
   // memory pipeline takes them at 64 bytes per clock, so issued back to back they hold the wave
@@ -789,7 +799,9 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     else dma16_s_if(req_mask, v_off[i], req_v, &sV[req_stage][q * 512]);
   };
   auto prepare_regular = [&](const Slot& s, int stage) {
-    const int64_t at = static_cast<int64_t>(s.kvh) * p.stride_head + static_cast<int64_t>(s.id) * blk_stride;
+    // (a block spans fewer than 2^31 elements: the host checks the slot stride)
+    const int64_t at = s.head_off + static_cast<int64_t>(static_cast<uint64_t>(static_cast<uint32_t>(s.id)) *
+                                                         static_cast<uint32_t>(blk_stride));
     req_k = kall + at;
     req_v = vall + at;
     req_stage = stage;
@@ -798,8 +810,8 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     // the tile that holds the frontier of its item (one per item, issued at once): rows past the
     // frontier may be unallocated or hold anything, they fetch the frontier row instead (finite
     // data, weight 0 after masking)
-    const uint16_t* kg = kall + static_cast<int64_t>(s.kvh) * p.stride_head;
-    const uint16_t* vg = vall + static_cast<int64_t>(s.kvh) * p.stride_head;
+    const uint16_t* kg = kall + s.head_off;
+    const uint16_t* vg = vall + s.head_off;
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
       const int q = wave * IPW + i;
@@ -822,41 +834,57 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
   };
 
   // ---- per-item state of the lane
-  bf16x8 qf[STEPS];
-  int lim_raw = 0;
-  int it_tok_head = 0, it_part = -1;
-  bool it_valid = false;
+  bf16x8 qf[RB][STEPS];
+  int lim_raw[RB];
+  int it_tok_head[RB], it_part = -1;
+  bool it_valid[RB];
   int it_rows_left = 0;                 // rows of the stream at and after this wave's first row
-  auto load_item = [&](const i32x8& d) {
-    const int row = d[2] + wave * 32 + n;
-    it_valid = row < d[1];
-    const int row_c = it_valid ? row : d[1] - 1;
-    const int tq = row_c / p.group;
-    const int tok = d[0] + tq;
-    it_tok_head = tok * p.n_q_heads + (d[3] & 255) * p.group + (row_c - tq * p.group);
-    it_part = d[7];
-    it_rows_left = d[1] - (d[2] + wave * 32);
-    const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + static_cast<int64_t>(it_tok_head) * D;
 #pragma unroll
-    for (int st = 0; st < STEPS; ++st)
-      qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(qrow + 16 * st + 8 * h));
-    lim_raw = p.q_pos[tok];
+  for (int rb = 0; rb < RB; ++rb) {
+    lim_raw[rb] = 0;
+    it_tok_head[rb] = 0;
+    it_valid[rb] = false;
+  }
+  auto load_item = [&](const i32x8& d) {
+    it_part = d[7];
+    it_rows_left = d[1] - (d[2] + wave * WROWS);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const int row = d[2] + wave * WROWS + rb * 32 + n;
+      it_valid[rb] = row < d[1];
+      const int row_c = it_valid[rb] ? row : d[1] - 1;
+      const int tq = row_c / p.group;
+      const int tok = d[0] + tq;
+      it_tok_head[rb] = tok * p.n_q_heads + (d[3] & 255) * p.group + (row_c - tq * p.group);
+      const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + static_cast<int64_t>(it_tok_head[rb]) * D;
+#pragma unroll
+      for (int st = 0; st < STEPS; ++st)
+        qf[rb][st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(qrow + 16 * st + 8 * h));
+      lim_raw[rb] = p.q_pos[tok];
+    }
   };
 
-  f32x16 o[DB];
+  f32x16 o[RB][DB];
+  float m_run[RB], l_run[RB];
+  int lim[RB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m_run = kNegInf, l_run = 0.f;
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[rb][db][r] = 0.f;
+    m_run[rb] = kNegInf;
+    l_run[rb] = 0.f;
+    lim[rb] = -1;
+  }
   const float slack = kMaxSlack / p.scale_log2e;
-  int lim = -1, wave_min = -1, wave_max = -1;
+  int wave_min = -1, wave_max = -1;
 
   auto compute = [&](int kt, int stage) {
     const int j0 = kt * kBN;
     const uint16_t* tK = sK[stage];
     const uint16_t* tV = sV[stage];
-    f32x16 sacc[2];
+    f32x16 sacc[RB][2];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     constexpr int KPF = 2;               // K fragments are read two steps ahead of their MFMAs
     bf16x8 ka[KPF + 1][2];
@@ -876,8 +904,10 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
       }
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st % (KPF + 1)][kb], qf[st],
-                                                           st == 0 ? zero16 : sacc[kb], 0, 0, 0);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          sacc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st % (KPF + 1)][kb], qf[rb][st],
+                                                                 st == 0 ? zero16 : sacc[rb][kb], 0, 0, 0);
       request_part_if(st);
     }
     // pin that order (the scheduler would otherwise pull each read back to just before its use)
@@ -885,53 +915,56 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
 #pragma unroll
     for (int st = 0; st < STEPS - KPF; ++st) {
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * RB, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2 * KPF, 0);
-    if (j0 + kBN - 1 > wave_min) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * RB * KPF, 0);
+    bf16x8 pb[RB][2][2];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      if (j0 + kBN - 1 > wave_min) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = j0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
+            if (key > lim[rb]) sacc[rb][kb][r] = kNegInf;
+          }
+      }
+      float t_max = kNegInf;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = j0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
-          if (key > lim) sacc[kb][r] = kNegInf;
-        }
-    }
-    float t_max = kNegInf;
+        for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[rb][kb][r]);
+      t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
+      if (__any(t_max > m_run[rb] + slack)) {
+        const bool up = t_max > m_run[rb] + slack;
+        const float m_new = up ? t_max : m_run[rb];
+        const float alpha = up ? __builtin_amdgcn_exp2f((m_run[rb] - m_new) * p.scale_log2e) : 1.f;
+        m_run[rb] = m_new;
+        l_run[rb] *= alpha;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[kb][r]);
-    t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
-    if (__any(t_max > m_run + slack)) {
-      const bool up = t_max > m_run + slack;
-      const float m_new = up ? t_max : m_run;
-      const float alpha = up ? __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e) : 1.f;
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-    }
-    const float m_scaled = (m_run == kNegInf ? 0.f : m_run) * p.scale_log2e;
-    bf16x8 pb[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int mm = 0; mm < 2; ++mm) {
-        cs::u32x4 w;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
-          const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
-          const uint32_t pk = pack_bf16x2(e0, e1);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
-                                                  __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run, false);
-          w[c] = pk;
-        }
-        pb[kb][mm] = __builtin_bit_cast(bf16x8, w);
+          for (int r = 0; r < 16; ++r) o[rb][db][r] *= alpha;
       }
+      const float m_scaled = (m_run[rb] == kNegInf ? 0.f : m_run[rb]) * p.scale_log2e;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+          cs::u32x4 w;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[rb][kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
+            const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[rb][kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
+            const uint32_t pk = pack_bf16x2(e0, e1);
+            l_run[rb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
+                                                        __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run[rb], false);
+            w[c] = pk;
+          }
+          pb[rb][kb][mm] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
     // 16 MFMAs, m = (key block, key half, d block); V^T fragments are read VPF MFMAs ahead
     constexpr int VPF = 3;
     s16x4 vlo[VPF + 1], vhi[VPF + 1];
@@ -946,49 +979,54 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     for (int m = 0; m < 16; ++m) {
       if (m + VPF < 16) v_frag(m + VPF);
       const s16x8 a = __builtin_shufflevector(vlo[m % (VPF + 1)], vhi[m % (VPF + 1)], 0, 1, 2, 3, 4, 5, 6, 7);
-      o[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb[m >> 3][(m >> 2) & 1],
-                                                        o[m & 3], 0, 0, 0);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        o[rb][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                              pb[rb][m >> 3][(m >> 2) & 1], o[rb][m & 3], 0, 0, 0);
     }
   };
 
   // Normalises and stores the rows of the finished item (or its un-normalised partial rows when
   // the key sweep is shared), then clears the accumulators.
-  auto finish_item = [&](int tok_head, bool valid, int part) {
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (part >= 0) {
-      const int64_t prow = static_cast<int64_t>(part) + wave * 32 + n;
-      if (h == 0) {
-        p.ws_ml[prow * 2] = m_run;
-        p.ws_ml[prow * 2 + 1] = l_tot;
+  auto finish_item = [&](const int (&tok_head)[RB], const bool (&valid)[RB], int part) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32);
+      if (part >= 0) {
+        const int64_t prow = static_cast<int64_t>(part) + wave * WROWS + rb * 32 + n;
+        if (h == 0) {
+          p.ws_ml[prow * 2] = m_run[rb];
+          p.ws_ml[prow * 2 + 1] = l_tot;
+        }
+        float* po = p.ws_o + prow * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const cs::u32x4 w = {__float_as_uint(o[rb][db][4 * rq + 0]), __float_as_uint(o[rb][db][4 * rq + 1]),
+                                 __float_as_uint(o[rb][db][4 * rq + 2]), __float_as_uint(o[rb][db][4 * rq + 3])};
+            *reinterpret_cast<cs::u32x4*>(po + 32 * db + 8 * rq + 4 * h) = w;
+          }
+      } else if (valid[rb]) {
+        const float inv = __builtin_amdgcn_rcpf(l_tot);      // 1 ulp: far below the bf16 result's rounding
+        uint16_t* orow = static_cast<uint16_t*>(p.out) + static_cast<int64_t>(tok_head[rb]) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            cs::u32x2 w;
+            w.x = pack_bf16x2(o[rb][db][4 * rq + 0] * inv, o[rb][db][4 * rq + 1] * inv);
+            w.y = pack_bf16x2(o[rb][db][4 * rq + 2] * inv, o[rb][db][4 * rq + 3] * inv);
+            *reinterpret_cast<cs::u32x2*>(orow + 32 * db + 8 * rq + 4 * h) = w;
+          }
       }
-      float* po = p.ws_o + prow * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const cs::u32x4 w = {__float_as_uint(o[db][4 * rq + 0]), __float_as_uint(o[db][4 * rq + 1]),
-                               __float_as_uint(o[db][4 * rq + 2]), __float_as_uint(o[db][4 * rq + 3])};
-          *reinterpret_cast<cs::u32x4*>(po + 32 * db + 8 * rq + 4 * h) = w;
-        }
-    } else if (valid) {
-      const float inv = 1.f / l_tot;
-      uint16_t* orow = static_cast<uint16_t*>(p.out) + static_cast<int64_t>(tok_head) * D;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          cs::u32x2 w;
-          w.x = pack_bf16x2(o[db][4 * rq + 0] * inv, o[db][4 * rq + 1] * inv);
-          w.y = pack_bf16x2(o[db][4 * rq + 2] * inv, o[db][4 * rq + 3] * inv);
-          *reinterpret_cast<cs::u32x2*>(orow + 32 * db + 8 * rq + 4 * h) = w;
-        }
+        for (int r = 0; r < 16; ++r) o[rb][db][r] = 0.f;
+      m_run[rb] = kNegInf;
+      l_run[rb] = 0.f;
     }
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    m_run = kNegInf;
-    l_run = 0.f;
   };
 
   // ---- prologue: first item, first tile request, block ids of the second slot
@@ -1000,8 +1038,13 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
   request_ids(nxt);
   load_item(d0);
   asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nxt.id), "+s"(nxt.last_id));
-  bool new_item = true, ep_pending = false, ep_valid = false;
-  int ep_tok_head = 0, ep_part = -1;
+  bool new_item = true, ep_pending = false, ep_valid[RB];
+  int ep_tok_head[RB], ep_part = -1;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    ep_valid[rb] = false;
+    ep_tok_head[rb] = 0;
+  }
   int stage = 0;
 
   for (;;) {
@@ -1010,14 +1053,19 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     // later, when that wait would also cover the tile request issued below)
     wait_vmcnt<0>();
 #pragma unroll
-    for (int st = 0; st < STEPS; ++st) asm volatile("" : "+v"(qf[st]));
-    asm volatile("" : "+v"(lim_raw));
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+      for (int st = 0; st < STEPS; ++st) asm volatile("" : "+v"(qf[rb][st]));
+      asm volatile("" : "+v"(lim_raw[rb]));
+    }
     __syncthreads();                     // every wave's share landed; every wave left the other stage
     if (new_item) {
-      lim = it_valid ? lim_raw : -1;
-      const int rows_here = min(32, it_rows_left);        // rows of this wave that exist
-      wave_min = rows_here > 0 ? __builtin_amdgcn_readlane(lim, 0) : -1;
-      wave_max = rows_here > 0 ? __builtin_amdgcn_readlane(lim, max(rows_here, 1) - 1) : -1;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) lim[rb] = it_valid[rb] ? lim_raw[rb] : -1;
+      const int rows_here = min(WROWS, it_rows_left);     // rows of this wave that exist
+      const int last = max(rows_here, 1) - 1;             // positions do not decrease along the rows
+      wave_min = rows_here > 0 ? __builtin_amdgcn_readlane(lim[0], 0) : -1;
+      wave_max = rows_here > 0 ? __builtin_amdgcn_readlane(lim[RB > 1 && last >= 32 ? RB - 1 : 0], last & 31) : -1;
       new_item = false;
     }
     // request the next tile: at once if it holds the frontier of its item or if this wave has
@@ -1051,8 +1099,11 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_stream_kernel(AttnPar
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nn.id), "+s"(nn.last_id), "+s"(d3));
     if (cur_last) {
       ep_pending = true;
-      ep_tok_head = it_tok_head;
-      ep_valid = it_valid;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        ep_tok_head[rb] = it_tok_head[rb];
+        ep_valid[rb] = it_valid[rb];
+      }
       ep_part = it_part;
       if ((d1[5] >> 16) > 0) {
         load_item(d1);
@@ -1187,6 +1238,7 @@ struct AttnPlan {
   int max_splits, max_tiles;
   int grid;              // persistent workgroups: 8 XCDs x up to 64
   int bm;                // rows per item
+  int rb;                // 32-row blocks per wave
   int hist_pitch;        // buckets of the planner's counting sort, per XCD
   size_t off_items, off_rt_desc, off_st_toff, off_st_work, off_st_rank, off_rt_stream, off_rt_wgmax,
       off_hist, off_ml, off_o, total;
@@ -1194,7 +1246,8 @@ struct AttnPlan {
 
 AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_heads, int32_t max_blocks) {
   AttnPlan a;
-  a.bm = kBM;
+  a.rb = 1;
+  a.bm = kBM * a.rb;
   a.r_cap = (n_q * group) / a.bm + n_streams;
   a.rt_cap = a.r_cap * n_kv_heads;
   a.max_tiles = static_cast<int>((static_cast<int64_t>(max_blocks) * CS_KV_BLOCK + kBN - 1) / kBN);
@@ -1211,7 +1264,8 @@ AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_h
   }
   a.items_cap = a.rt_cap * a.max_splits;
   const int64_t per_xcd = (a.items_cap + 7) / 8;
-  a.grid = 8 * static_cast<int>(per_xcd < 64 ? per_xcd : 64);
+  const int64_t cap = a.rb == 2 ? 32 : 64;
+  a.grid = 8 * static_cast<int>(per_xcd < cap ? per_xcd : cap);
   size_t at = kPlanHeaderInts * sizeof(int32_t);
   auto take = [&](size_t bytes) {
     const size_t here = (at + 255) & ~static_cast<size_t>(255);
@@ -1341,7 +1395,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         if (e != CS_OK) return e;
         if (plan_mode == CS_ATTN_PLAN_ONLY) return CS_OK;
       }
-      hipLaunchKernelGGL(window_attn_bf16_stream_kernel, dim3(static_cast<unsigned>(a.grid)), dim3(256), 0, st, p);
+      hipLaunchKernelGGL(window_attn_bf16_stream_kernel<1>, dim3(static_cast<unsigned>(a.grid)), dim3(256), 0, st, p);
       if (a.max_splits > 1) {
         const int e = cs::note_hip(hipGetLastError());
         if (e != CS_OK) return e;
