@@ -341,18 +341,15 @@ __device__ __forceinline__ void dma16_s(uint32_t off, const void* sbase, const v
                : "memory", "m0");
 }
 
-// ... and under a wave-uniform predicate applied through the execution mask (mask 0: the
-// instruction issues with no lane active and moves nothing), so that a request can be interleaved
-// with a block of MFMAs without a branch splitting that block.
-__device__ __forceinline__ void dma16_s_if(uint64_t mask, uint32_t off, const void* sbase, const void* lds_dst) {
-  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)lds_dst));
-  uint64_t saved;
-  asm volatile(
-      "s_mov_b64 %0, exec\n\ts_and_b64 exec, exec, %4\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0"
-      : "=&s"(saved)
-      : "v"(off), "s"(sbase), "s"(lds_addr), "s"(mask)
-      : "memory", "m0", "scc");
+// ... and with the LDS destination given as a byte address in an SGPR.
+__device__ __forceinline__ uint32_t lds_address(const void* lds_ptr) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)lds_ptr));
+}
+__device__ __forceinline__ void dma16_sa(uint32_t off, const void* sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(off), "s"(sbase), "s"(lds_addr)
+               : "memory", "m0");
 }
 
 template <int N>
@@ -705,6 +702,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
 
   __shared__ __attribute__((aligned(1024))) uint16_t sK[2][TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t sV[2][TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t s_sink[4][512];   // see request_part
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -784,19 +782,26 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   // memory pipeline takes them at 64 bytes per clock, so issued back to back they hold the wave
   // for hundreds of cycles: regular tiles are issued one instruction at a time between the MFMAs
   // of the S phase instead (request_part), with a wave-uniform base in SGPRs and the lane's
-  // constant 32-bit offset.
+  // constant 32-bit offset.  The S phase always issues its eight parts, so that no branch or
+  // predicate splits the block of MFMAs: when there is nothing to request (the next tile holds a
+  // frontier and went out at once, or there is no next tile) the parts re-read the current
+  // tile's cache block into a 1-KiB sink.
   const uint16_t *req_k = nullptr, *req_v = nullptr;
-  int req_stage = 0;
-  uint64_t req_mask = 0;                // all ones while a spread request is pending
+  uint32_t req_dst_k = 0, req_dst_v = 0, req_step = 0;
+  const uint32_t lds_k0 = lds_address(&sK[0][wave * IPW * 512]), lds_v0 = lds_address(&sV[0][wave * IPW * 512]);
+  const uint32_t lds_sink = lds_address(&s_sink[wave][0]);
   auto request_part = [&](int part) {
-    const int i = part & 3, q = wave * IPW + i;
-    if (part < 4) dma16_s(k_off[i], req_k, &sK[req_stage][q * 512]);
-    else dma16_s(v_off[i], req_v, &sV[req_stage][q * 512]);
+    const int i = part & 3;
+    if (part < 4) dma16_sa(k_off[i], req_k, req_dst_k + i * req_step);
+    else dma16_sa(v_off[i], req_v, req_dst_v + i * req_step);
   };
-  auto request_part_if = [&](int part) {
-    const int i = part & 3, q = wave * IPW + i;
-    if (part < 4) dma16_s_if(req_mask, k_off[i], req_k, &sK[req_stage][q * 512]);
-    else dma16_s_if(req_mask, v_off[i], req_v, &sV[req_stage][q * 512]);
+  auto prepare_sink = [&](const Slot& s) {
+    const int64_t at = s.head_off + static_cast<int64_t>(static_cast<uint64_t>(static_cast<uint32_t>(s.id)) *
+                                                         static_cast<uint32_t>(blk_stride));
+    req_k = kall + at;
+    req_v = vall + at;
+    req_dst_k = req_dst_v = lds_sink;
+    req_step = 0;
   };
   auto prepare_regular = [&](const Slot& s, int stage) {
     // (a block spans fewer than 2^31 elements: the host checks the slot stride)
@@ -804,7 +809,9 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
                                                          static_cast<uint32_t>(blk_stride));
     req_k = kall + at;
     req_v = vall + at;
-    req_stage = stage;
+    req_dst_k = lds_k0 + stage * (TILE * 2);
+    req_dst_v = lds_v0 + stage * (TILE * 2);
+    req_step = 1024;
   };
   auto issue_frontier = [&](const Slot& s, int stage) {
     // the tile that holds the frontier of its item (one per item, issued at once): rows past the
@@ -908,7 +915,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
         for (int rb = 0; rb < RB; ++rb)
           sacc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st % (KPF + 1)][kb], qf[rb][st],
                                                                  st == 0 ? zero16 : sacc[rb][kb], 0, 0, 0);
-      request_part_if(st);
+      request_part(st);
     }
     // pin that order (the scheduler would otherwise pull each read back to just before its use)
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * KPF, 0);
@@ -1071,14 +1078,11 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
     // request the next tile: at once if it holds the frontier of its item or if this wave has
     // nothing to compute in this step, else spread over the S phase of this step
     const bool computes = cur.kt * kBN <= wave_max;
-    req_mask = 0;
-    if (nxt.live) {
-      if (computes && nxt.kt != nxt.wg_max / kBN) {
-        prepare_regular(nxt, stage ^ 1);
-        req_mask = ~0ull;
-      } else {
-        issue(nxt, stage ^ 1);
-      }
+    if (nxt.live && computes && nxt.kt != nxt.wg_max / kBN) {
+      prepare_regular(nxt, stage ^ 1);
+    } else {
+      if (nxt.live) issue(nxt, stage ^ 1);
+      prepare_sink(cur);
     }
 
     // scalar requests for later steps: block ids of the slot after next; at the last tile of an
