@@ -386,10 +386,14 @@ typedef __attribute__((ext_vector_type(8))) int32_t i32x8;
 // the item the same workgroup takes next (-1: none), [7] first row of the item's partial result in
 // the workspace, or -1 when the item covers the whole sweep and writes `out`.
 // Plan header (ints): [0..8] list offsets per XCD, [9] row tiles, [16..23] end item,
-// [32 + 4 (64 x + j) + k] k-th item (k = 0, 1, 2) of workgroup j of XCD x (-1: none).
+// then one 32-int entry per workgroup j of XCD x at [32 + 32 (64 x + j)]: [0..2] its first three
+// items (-1: none), [3] cache block of its first item's frontier, [4..7] cache blocks of its first
+// tile request (one per wave), [8..15] a copy of its first item's descriptor, [16] its item count.
+// With the entry a workgroup can send its first tile request after ONE dependent load.
 constexpr int kSlotsPerXcd = 64;      // persistent workgroups per XCD: 32 CUs x 2
 constexpr int kHdrEndItem = 16, kHdrHeads = 32;
-constexpr int kPlanHeaderInts = kHdrHeads + 4 * 8 * kSlotsPerXcd;
+constexpr int kHdrEntryInts = 32;
+constexpr int kPlanHeaderInts = kHdrHeads + kHdrEntryInts * 8 * kSlotsPerXcd;
 constexpr int kItemFixedCostHalves = 3;  // per-item overhead in half key tiles, for the planner's balance
 constexpr int kPlanThreads = 1024;
 constexpr int kSortMax = 2048;        // streams sorted by work in LDS; beyond, stream order is kept
@@ -397,6 +401,8 @@ constexpr int kSortMax = 2048;        // streams sorted by work in LDS; beyond, 
 struct PlanParams {
   const int32_t* __restrict__ cu_q;
   const int32_t* __restrict__ q_pos;
+  const int32_t* __restrict__ block_table;
+  int32_t max_blocks;
   int32_t n_streams, group, n_kv_heads, chunk_tiles, max_splits, max_tiles, r_cap, bm, n_slots, hist_pitch;   // n_slots: workgroups per XCD
   int32_t* header;      // [kPlanHeaderInts]
   int32_t* items;       // [items_cap][8]
@@ -667,8 +673,22 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
         }
       }
       if (lane < kSlotsPerXcd) {
-        int32_t* hd = pp.header + kHdrHeads + 4 * (w * kSlotsPerXcd + lane);
-        hd[0] = first3[0]; hd[1] = first3[1]; hd[2] = first3[2]; hd[3] = taken;
+        int32_t* hd = pp.header + kHdrHeads + kHdrEntryInts * (w * kSlotsPerXcd + lane);
+        int32_t d[8] = {0, 0, 0, 0, -1, 0, -1, -1};       // the end item
+        int32_t ids[4] = {0, 0, 0, 0}, last_id = 0;
+        if (taken > 0) {
+          for (int i = 0; i < 8; ++i)
+            d[i] = __hip_atomic_load(&pp.items[static_cast<int64_t>(first3[0]) * 8 + i], __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+          const int32_t* row = pp.block_table + static_cast<int64_t>(d[3] >> 8) * pp.max_blocks;
+          const int last_blk = d[4] >> 4;
+          for (int i = 0; i < 4; ++i) ids[i] = row[min((d[5] & 0xffff) * 4 + i, last_blk)];
+          last_id = row[last_blk];
+        }
+        hd[0] = first3[0]; hd[1] = first3[1]; hd[2] = first3[2]; hd[3] = last_id;
+        for (int i = 0; i < 4; ++i) hd[4 + i] = ids[i];
+        for (int i = 0; i < 8; ++i) hd[8 + i] = d[i];
+        hd[16] = taken;
       }
     }
   }
@@ -714,10 +734,11 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   auto item_at = [&](int idx) -> const int32_t* {
     return idx >= 0 ? p.ws_items + static_cast<int64_t>(idx) * 8 : p.ws_plan + kHdrEndItem;
   };
-  const int32_t* heads = p.ws_plan + kHdrHeads + 4 * (xcd * kSlotsPerXcd + slot_j);
-  i32x8 d0 = sload8(item_at(heads[0])), d1 = sload8(item_at(heads[1])), d2 = sload8(item_at(heads[2]));
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d0), "+s"(d1), "+s"(d2));
+  const int32_t* entry = p.ws_plan + kHdrHeads + kHdrEntryInts * (xcd * kSlotsPerXcd + slot_j);
+  i32x8 e0 = sload8(entry), d0 = sload8(entry + 8);
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(e0), "+s"(d0));
   if ((d0[5] >> 16) == 0) return;       // nothing for this workgroup
+  i32x8 d1 = sload8(item_at(e0[1])), d2 = sload8(item_at(e0[2]));   // waited for after the first tile request
   int seq0 = 0;                         // d0 is the seq0-th item of this workgroup
 
   // ---- constants of the lane: DMA sources inside a cache block, LDS read addresses
@@ -1038,9 +1059,10 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
 
   // ---- prologue: first item, first tile request, block ids of the second slot
   Slot cur = first_slot(d0, 0);
-  request_ids(cur);
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(cur.id), "+s"(cur.last_id));
+  cur.id = wave == 0 ? e0[4] : wave == 1 ? e0[5] : wave == 2 ? e0[6] : e0[7];
+  cur.last_id = e0[3];
   issue(cur, 0);
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d1), "+s"(d2));
   Slot nxt = successor(cur);
   request_ids(nxt);
   load_item(d0);
@@ -1375,6 +1397,8 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         PlanParams pp;
         pp.cu_q = cu_q;
         pp.q_pos = q_pos;
+        pp.block_table = block_table;
+        pp.max_blocks = max_blocks;
         pp.n_streams = n_streams;
         pp.group = group;
         pp.n_kv_heads = n_kv_heads;
