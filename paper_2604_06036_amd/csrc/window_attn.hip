@@ -602,7 +602,10 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   __threadfence_block();
   __syncthreads();
 
-  // ---- write the items
+  // ---- write the items (row-tile slots beyond the planned ones are marked unsplit, so that the
+  //      merge kernel needs no other bound than the size of its grid)
+  for (int i = n_rt * pp.n_kv_heads + tid; i < pp.r_cap * pp.n_kv_heads; i += kPlanThreads)
+    pp.rt_desc[static_cast<int64_t>(i) * 8 + 4] = 0;
   for (int r = tid; r < n_rt; r += kPlanThreads) {
     const int s = pp.rt_stream[r];
     const int t = r - pp.st_toff[s];
@@ -1151,8 +1154,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
 __global__ __launch_bounds__(256) void window_attn_merge_kernel(AttnParams p) {
   constexpr int D = 128;
   const int groups = p.bm / 8;
-  const int item = blockIdx.x / groups;
-  if (item >= p.ws_plan[9]) return;
+  const int item = blockIdx.x / groups;              // < the row-tile capacity the grid was sized for
   const int32_t* d = p.ws_desc + item * 8;
   const int n_split = d[4];
   if (n_split <= 1) return;
@@ -1162,18 +1164,30 @@ __global__ __launch_bounds__(256) void window_attn_merge_kernel(AttnParams p) {
   const int row = r_tile + rl;
   if (row >= rows_total) return;
   const int64_t base = static_cast<int64_t>(item) * p.max_splits * p.bm + rl;
-  float m_all = kNegInf;
-  for (int c = 0; c < n_split; ++c) m_all = fmaxf(m_all, p.ws_ml[(base + static_cast<int64_t>(c) * p.bm) * 2]);
-  float acc[4] = {0.f, 0.f, 0.f, 0.f}, l_all = 0.f;
-  for (int c = 0; c < n_split; ++c) {
-    const int64_t pr = base + static_cast<int64_t>(c) * p.bm;
-    const float m_c = p.ws_ml[pr * 2];
-    if (m_c == kNegInf) continue;                      // this key range held nothing visible
-    const float w = __builtin_amdgcn_exp2f((m_c - m_all) * p.scale_log2e);
-    l_all = fmaf(w, p.ws_ml[pr * 2 + 1], l_all);
-    const float4 t = *reinterpret_cast<const float4*>(p.ws_o + pr * D + 4 * sub);
-    acc[0] = fmaf(w, t.x, acc[0]); acc[1] = fmaf(w, t.y, acc[1]);
-    acc[2] = fmaf(w, t.z, acc[2]); acc[3] = fmaf(w, t.w, acc[3]);
+  // one pass, four key ranges at a time: all loads of a batch are independent of each other and
+  // of the running maximum (rows a range did not see hold m = -inf, l = 0, O = 0)
+  float m_all = kNegInf, l_all = 0.f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int c0 = 0; c0 < n_split; c0 += 4) {
+    float2 ml[4];
+    float4 t[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t pr = base + static_cast<int64_t>(min(c0 + u, n_split - 1)) * p.bm;
+      ml[u] = *reinterpret_cast<const float2*>(p.ws_ml + pr * 2);
+      t[u] = *reinterpret_cast<const float4*>(p.ws_o + pr * D + 4 * sub);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (c0 + u >= n_split || ml[u].x == kNegInf) continue;
+      const float m_new = fmaxf(m_all, ml[u].x);
+      const float a = m_all == kNegInf ? 0.f : __builtin_amdgcn_exp2f((m_all - m_new) * p.scale_log2e);
+      const float w = __builtin_amdgcn_exp2f((ml[u].x - m_new) * p.scale_log2e);
+      m_all = m_new;
+      l_all = fmaf(w, ml[u].y, l_all * a);
+      acc[0] = fmaf(w, t[u].x, acc[0] * a); acc[1] = fmaf(w, t[u].y, acc[1] * a);
+      acc[2] = fmaf(w, t[u].z, acc[2] * a); acc[3] = fmaf(w, t[u].w, acc[3] * a);
+    }
   }
   const float inv = 1.f / l_all;
   const int tok = q0 + row / p.group;
