@@ -56,8 +56,8 @@ extern "C" {
 /* cs_window_prefill_attn: what the workspace holds when the call starts */
 #define CS_ATTN_PLAN_BUILD 0   /* nothing: plan the work from cu_q / q_pos, then run              */
 #define CS_ATTN_PLAN_REUSE 1   /* the plan an earlier BUILD call left there (same workspace, same
-                                  cu_q / q_pos / block_table contents and shape arguments): run
-                                  straight away                                                    */
+                                  cu_q / q_pos / block_table contents and shape arguments):
+                                  run straight away                                              */
 #define CS_ATTN_PLAN_ONLY  2   /* nothing: plan the work and return without computing attention   */
 
 /* Library identification, e.g. "codecsight-mi355x 0.1 (gfx950)". Static storage. */
@@ -189,21 +189,22 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  *  workspace     cs_window_prefill_attn_workspace() bytes for the same shape arguments, 16-byte
  *                aligned (may be 0, then NULL is accepted).  Holds the work plan of the launch
  *                (the list of (stream, kv head, row tile, key range) items each XCD serves, a
- *                function of cu_q, q_pos and block_table only) and the partial results of row tiles whose
- *                key sweep is shared by several items.  Two calls that overlap in time must not
- *                share a workspace.
+ *                function of cu_q, q_pos and block_table only) and the partial results of row
+ *                tiles whose key sweep is shared by several items.  Two calls that overlap in
+ *                time must not share a workspace.
  *  plan_mode     CS_ATTN_PLAN_BUILD: workspace contents need not be initialised; the call plans
  *                and runs.  CS_ATTN_PLAN_REUSE: the workspace still holds the plan of an earlier
- *                BUILD call with identical cu_q / q_pos / block_table contents and shape arguments (the decoder
- *                layers of one step: build at the first layer, reuse at the others); the
- *                planning launch is skipped.  CS_ATTN_PLAN_ONLY: plan and return (q, the caches
+ *                BUILD call with identical cu_q / q_pos / block_table contents and shape
+ *                arguments (the decoder layers of one step: build at the first layer, reuse at
+ *                the others); the planning launch is skipped.  CS_ATTN_PLAN_ONLY: plan and return (q, the caches
  *                and out are not touched and may be NULL), for callers that prefer every layer
  *                to run in REUSE mode.  Ignored where no plan is used (CS_F32, head_dim 64: an
  *                ONLY call then computes like any other).
  * Errors: CS_EINVAL (null pointer, negative size, n_q_heads not a multiple of n_kv_heads, unknown
  *         plan_mode), CS_EUNSUPPORTED (head_dim not in {64,128}, block_size != 16,
  *         n_q_heads/n_kv_heads > 16, strides not multiples of 16 bytes, unknown dtype; CS_BF16:
- *         n_kv_heads > 256, n_streams >= 2^23, max_blocks > 8192 with head_dim 64),
+ *         n_kv_heads > 256, n_streams >= 2^23, stride_slot >= 2^26 elements or max_blocks >= 2^17
+ *         with head_dim 128, max_blocks > 8192 with head_dim 64),
  *         CS_EWORKSPACE, CS_EHIP.
  *         n_q == 0 or n_streams == 0 returns CS_OK.
  * ------------------------------------------------------------------------------------------ */
