@@ -196,9 +196,9 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  *                and runs.  CS_ATTN_PLAN_REUSE: the workspace still holds the plan of an earlier
  *                BUILD call with identical cu_q / q_pos / block_table contents and shape
  *                arguments (the decoder layers of one step: build at the first layer, reuse at
- *                the others); the planning launch is skipped.  CS_ATTN_PLAN_ONLY: plan and return (q, the caches
- *                and out are not touched and may be NULL), for callers that prefer every layer
- *                to run in REUSE mode.  Ignored where no plan is used (CS_F32, head_dim 64: an
+ *                the others); the planning launch is skipped.  CS_ATTN_PLAN_ONLY: plan and return
+ *                (q, the caches and out are not touched and may be NULL), for callers that
+ *                prefer every layer to run in REUSE mode.  Ignored where no plan is used (CS_F32, head_dim 64: an
  *                ONLY call then computes like any other).
  * Errors: CS_EINVAL (null pointer, negative size, n_q_heads not a multiple of n_kv_heads, unknown
  *         plan_mode), CS_EUNSUPPORTED (head_dim not in {64,128}, block_size != 16,
