@@ -27,8 +27,6 @@
 // per lane and a final cross-lane merge.  It exists for fp32 caches (small validation shapes).
 #include <math.h>
 
-#include <type_traits>
-
 #include "common.h"
 
 namespace {
@@ -437,23 +435,6 @@ __device__ __forceinline__ int plan_block_scan(int v, int* s_wave, int& total) {
   return base + incl - v;
 }
 
-// Minimum of an unsigned value over the 64 lanes of a wave by DPP row shifts and row broadcasts
-// (a chain of six ds_bpermute shuffles costs several hundred cycles; this costs a few dozen).
-__device__ __forceinline__ uint32_t plan_wave_umin(uint32_t v) {
-  auto step = [&](auto ctrl, auto row_mask) {
-    const uint32_t t = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
-        static_cast<int>(0xffffffffu), static_cast<int>(v), decltype(ctrl)::value, decltype(row_mask)::value, 0xf, false));
-    v = t < v ? t : v;
-  };
-  step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xf>{});   // row_shr:1
-  step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xf>{});   // row_shr:2
-  step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xf>{});   // row_shr:4
-  step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xf>{});   // row_shr:8
-  step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast:15
-  step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast:31
-  return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
-}
-
 __device__ __forceinline__ int plan_xcd_of_pair(int pair) {
   const int round = pair >> 3, pos = pair & 7;
   return (round & 1) ? 7 - pos : pos;
@@ -463,6 +444,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   __shared__ int s_wave[kPlanThreads / 64];
   __shared__ unsigned long long s_key[kSortMax];
   __shared__ int s_list_off[9];
+  __shared__ int s_by_rank[8][64];      // deal: lane (and length) of the item of each rank, per XCD
   const int tid = threadIdx.x;
   const int hist_pitch = pp.hist_pitch;
 
@@ -640,40 +622,48 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   __threadfence_block();
   __syncthreads();
 
-  // ---- deal every XCD's list to its workgroups (one wave per XCD, a lane per workgroup): items
-  //      in list order, each to the workgroup with the least work so far -- the schedule a run-time
-  //      queue would produce, fixed here so that the attention kernel needs no atomics.  Items of
-  //      one workgroup are chained through their `next` field.
+  // ---- deal every XCD's list to its workgroups (one wave per XCD, a lane per workgroup), a batch
+  //      of as many items as there are workgroups at a time: within a batch the longest item goes
+  //      to the workgroup with the least work so far, the second longest to the next one, ...
+  //      (ranks by counting, 64 lane reads each).  This is close to the schedule a run-time queue
+  //      would produce, fixed here so that the attention kernel needs no atomics.  Items of one
+  //      workgroup are chained through their `next` field.
   {
     const int w = tid >> 6, lane = tid & 63;
     if (w < 8) {
       const int begin = s_list_off[w], end = s_list_off[w + 1];
-      // work so far in half key tiles, with the lane number below it: the minimum names the winner
-      uint32_t load = lane < pp.n_slots ? static_cast<uint32_t>(lane) : 0xffffffffu;
+      const int n_wg = min(pp.n_slots, 64);
+      int load = lane < n_wg ? 0 : 0x7fffffff;          // half key tiles; lanes beyond the grid rank last
       int last = -1, first3[3] = {-1, -1, -1}, taken = 0;
-      for (int base = begin; base < end; base += 64) {
-        const int mine = base + lane;
-        int len = 0;
-        if (mine < end) {
-          const int kbe = __hip_atomic_load(&pp.items[static_cast<int64_t>(mine) * 8 + 5], __ATOMIC_RELAXED,
+      for (int base = begin; base < end; base += n_wg) {
+        const int n_here = min(n_wg, end - base);
+        int len = -1;                                     // lanes without an item rank last
+        if (lane < n_here) {
+          const int kbe = __hip_atomic_load(&pp.items[static_cast<int64_t>(base + lane) * 8 + 5], __ATOMIC_RELAXED,
                                             __HIP_MEMORY_SCOPE_AGENT);
           len = (kbe >> 16) - (kbe & 0xffff);
         }
-        const int n_here = min(64, end - base);
-        for (int k = 0; k < n_here; ++k) {
-          const uint32_t cost = static_cast<uint32_t>(2 * __builtin_amdgcn_readlane(len, k) + kItemFixedCostHalves) << 6;
-          const int winner = static_cast<int>(plan_wave_umin(load) & 63u);
-          if (lane == winner) {
-            const int idx = base + k;
-            if (last >= 0) pp.items[static_cast<int64_t>(last) * 8 + 6] = idx;
-            if (taken == 0) first3[0] = idx;
-            if (taken == 1) first3[1] = idx;
-            if (taken == 2) first3[2] = idx;
-            ++taken;
-            last = idx;
-            load += cost;
-          }
+        int item_rank = 0, load_rank = 0;                 // by decreasing length / increasing load, ties by lane
+#pragma unroll 8
+        for (int j = 0; j < 64; ++j) {
+          const int lj = __builtin_amdgcn_readlane(len, j), wj = __builtin_amdgcn_readlane(load, j);
+          item_rank += (lj > len || (lj == len && j < lane)) ? 1 : 0;
+          load_rank += (wj < load || (wj == load && j < lane)) ? 1 : 0;
         }
+        s_by_rank[w][item_rank] = lane | (len << 8);
+        __builtin_amdgcn_wave_barrier();
+        if (load_rank < n_here) {
+          const int got = s_by_rank[w][load_rank];
+          const int idx = base + (got & 255);
+          if (last >= 0) pp.items[static_cast<int64_t>(last) * 8 + 6] = idx;
+          if (taken == 0) first3[0] = idx;
+          if (taken == 1) first3[1] = idx;
+          if (taken == 2) first3[2] = idx;
+          ++taken;
+          last = idx;
+          load += 2 * (got >> 8) + kItemFixedCostHalves;
+        }
+        __builtin_amdgcn_wave_barrier();
       }
       if (lane < kSlotsPerXcd) {
         int32_t* hd = pp.header + kHdrHeads + kHdrEntryInts * (w * kSlotsPerXcd + lane);
