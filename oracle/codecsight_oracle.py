@@ -141,6 +141,44 @@ def rerotate(k_cache, v_cache, src_slot, dst_slot, delta, base, style=0):
     return k_rows, v_rows
 
 
+def rotate_axes(x, pos3, axis_of_pair, base, style=0):
+    """Multidimensional RoPE (Sec. 3.4.2: "the correction follows the model's mapping from
+    positional components to rotary dimensions").  A position is a triple (t, h, w); frequency
+    pair i, with the same theta_i as 1-D RoPE, is driven by component axis_of_pair[i]:
+
+        angle_i = pos3[..., axis_of_pair[i]] * theta_i
+
+    x [..., d]; pos3 broadcastable to x[..., 0] + (3,); axis_of_pair int [d/2] with values 0..2.
+    As with `rotate`, applied to a shift p_new - p_old it is the correction of Eq. 6, because
+    rotations of one pair by different angles compose by adding the angles.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    ia, ib = _pair_index(d, style)
+    axis = np.asarray(axis_of_pair, dtype=np.int64)
+    assert axis.shape == (d // 2,) and axis.min() >= 0 and axis.max() <= 2
+    pos_of_pair = np.asarray(pos3, dtype=np.float64)[..., axis]          # [..., d/2]
+    ang = pos_of_pair * rope_frequencies(d, base)
+    c, s = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    out[..., ia] = x[..., ia] * c - x[..., ib] * s
+    out[..., ib] = x[..., ib] * c + x[..., ia] * s
+    return out
+
+
+def rerotate_axes(k_cache, v_cache, src_slot, dst_slot, delta3, axis_of_pair, base, style=0):
+    """Eq. 6 on a KV pool for multidimensional RoPE: delta3 int [n_rows, 3] is the per-row shift
+    (d_t, d_h, d_w).  Same return convention as `rerotate`."""
+    src = np.asarray(src_slot, dtype=np.int64)
+    k_src = np.asarray(k_cache)[:, src].astype(np.float64)          # [L, n, Hkv, d]
+    d3 = np.asarray(delta3, dtype=np.float64)[None, :, None, :]     # [1, n, 1, 3]
+    k_rows = np.transpose(rotate_axes(k_src, d3, axis_of_pair, base, style), (1, 0, 2, 3))
+    v_rows = None
+    if dst_slot is not None:
+        v_rows = np.transpose(np.asarray(v_cache)[:, src].astype(np.float64), (1, 0, 2, 3))
+    return k_rows, v_rows
+
+
 # --------------------------------------------------------------------------------------------
 # (c) refresh write        Sec. 3.5: new K/V rows go straight into the destination cache
 # --------------------------------------------------------------------------------------------

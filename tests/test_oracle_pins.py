@@ -311,6 +311,103 @@ def test_rerotate_on_a_pool_moves_the_right_rows_and_leaves_values_alone():
     assert v_none is None and np.array_equal(k_rows2, k_rows)
 
 
+# ------------------------------------------------------------------ multi-axis RoPE (Sec. 3.4.2)
+def _sections_axis_map(sections):
+    return np.concatenate([np.full(n, a, np.int64) for a, n in enumerate(sections)])
+
+
+def test_axes_rotation_known_values_and_untouched_pairs():
+    # d = 4, base 1e4: theta = (1, 0.01); pair 0 follows h, pair 1 follows w; position (t,h,w) = (7, 2, 50)
+    x = np.array([1.0, 0.0, 0.0, 1.0])                    # half-split pairs: (x0, x2), (x1, x3)
+    got = oc.rotate_axes(x, np.array([7, 2, 50]), np.array([1, 2]), 1e4, style=0)
+    assert np.allclose(got, [math.cos(2.0), -math.sin(0.5), math.sin(2.0), math.cos(0.5)], atol=1e-15)
+    # a shift along t only leaves the pairs of the other axes exactly as they were
+    rng = np.random.default_rng(21)
+    d = 16
+    axis = _sections_axis_map([2, 3, 3])
+    y = rng.normal(size=(5, d))
+    z = oc.rotate_axes(y, np.array([-256, 0, 0]), axis, 1e6)
+    ia, ib = np.arange(d // 2), np.arange(d // 2) + d // 2
+    keep = axis != 0
+    assert np.array_equal(z[:, ia[keep]], y[:, ia[keep]]) and np.array_equal(z[:, ib[keep]], y[:, ib[keep]])
+    assert not np.allclose(z[:, ia[~keep]], y[:, ia[~keep]])
+
+
+def test_axes_rotation_with_one_axis_is_plain_rope():
+    rng = np.random.default_rng(22)
+    d, base = 32, 1e4
+    x = rng.normal(size=(6, d))
+    pos = rng.integers(-3000, 3000, size=6)
+    for a in range(3):
+        pos3 = rng.integers(-99, 99, size=(6, 3))
+        pos3[:, a] = pos
+        for style in (0, 1):
+            got = oc.rotate_axes(x, pos3, np.full(d // 2, a), base, style)
+            assert np.allclose(got, oc.rotate(x, pos, base, style), atol=1e-12)
+
+
+def test_axes_correction_equals_recomputation_and_keeps_relative_scores():
+    rng = np.random.default_rng(23)
+    d, base = 32, 1e6
+    axis = _sections_axis_map([4, 6, 6])
+    k_raw, q_raw = rng.normal(size=(9, d)), rng.normal(size=(9, d))
+    p_old = rng.integers(0, 4000, size=(9, 3))
+    p_new = p_old + rng.integers(-2500, 2500, size=(9, 3))
+    for style in (0, 1):
+        cached = oc.rotate_axes(k_raw, p_old, axis, base, style)
+        fixed = oc.rotate_axes(cached, p_new - p_old, axis, base, style)          # Eq. 6
+        assert np.allclose(fixed, oc.rotate_axes(k_raw, p_new, axis, base, style), atol=1e-9)
+        # undoing the old rotation and applying the new one, written as two steps
+        undone = oc.rotate_axes(cached, -p_old, axis, base, style)
+        assert np.allclose(undone, k_raw, atol=1e-9)
+        # scores depend on the per-axis position difference only
+        p_q = rng.integers(0, 4000, size=(9, 3))
+        shift = np.array([123, -45, 6])
+        s0 = np.sum(oc.rotate_axes(q_raw, p_q, axis, base, style) * oc.rotate_axes(k_raw, p_new, axis, base, style), -1)
+        s1 = np.sum(oc.rotate_axes(q_raw, p_q + shift, axis, base, style) *
+                    oc.rotate_axes(k_raw, p_new + shift, axis, base, style), -1)
+        assert np.allclose(s0, s1, atol=1e-8)
+
+
+def test_axes_rotation_against_transformers_multimodal_helper():
+    torch = pytest.importorskip("torch")
+    mod = pytest.importorskip("transformers.models.qwen2_vl.modeling_qwen2_vl")
+    d, base, n = 32, 1e4, 7
+    sections = [4, 6, 6]
+    rng = np.random.default_rng(24)
+    x = rng.normal(size=(1, 1, n, d))
+    pos3 = rng.integers(0, 900, size=(n, 3))
+    inv = 1.0 / (base ** (np.arange(0, d, 2, dtype=np.float64) / d))
+    ang = pos3.T[:, None, :, None] * inv                  # [3, 1, n, d/2]: every axis at every frequency
+    emb = np.concatenate([ang, ang], axis=-1)
+    cos, sin = torch.from_numpy(np.cos(emb)), torch.from_numpy(np.sin(emb))
+    xt = torch.from_numpy(x)
+    want, _ = mod.apply_multimodal_rotary_pos_emb(xt, xt, cos, sin, sections)
+    got = oc.rotate_axes(x[0, 0], pos3, _sections_axis_map(sections), base, style=0)
+    assert np.allclose(got, want[0, 0].numpy(), atol=1e-12)
+
+
+def test_rerotate_axes_on_a_pool():
+    rng = np.random.default_rng(25)
+    n_layers, n_slots, n_heads, d, base = 2, 30, 2, 16, 1e4
+    axis = _sections_axis_map([2, 3, 3])
+    k = rng.normal(size=(n_layers, n_slots, n_heads, d)).astype(np.float32)
+    v = rng.normal(size=(n_layers, n_slots, n_heads, d)).astype(np.float32)
+    src, dst = np.array([4, 29, 11], np.int32), np.array([0, 1, 2], np.int32)
+    delta3 = np.array([[-256, 0, 0], [3, -2, 7], [0, 0, 0]], np.int32)
+    k_rows, v_rows = oc.rerotate_axes(k, v, src, dst, delta3, axis, base)
+    for r in range(3):
+        for l in range(n_layers):
+            want = oc.rotate_axes(k[l, src[r]].astype(np.float64), delta3[r], axis, base)
+            assert np.allclose(k_rows[r, l], want, atol=1e-13)
+            assert np.array_equal(v_rows[r, l], v[l, src[r]].astype(np.float64))
+    assert np.array_equal(k_rows[2], k[:, 11].astype(np.float64))
+    # a time-only shift with every pair on the time axis is the one-dimensional correction
+    k1, _ = oc.rerotate(k, v, src, dst, delta3[:, 0], base)
+    k3, _ = oc.rerotate_axes(k, v, src, dst, delta3 * np.array([1, 0, 0]), np.zeros(d // 2, np.int64), base)
+    assert np.allclose(k1, k3, atol=1e-13)
+
+
 # ------------------------------------------------------------------ (c) scatter
 def test_scatter_writes_targets_and_nothing_else():
     rng = np.random.default_rng(20)
