@@ -125,6 +125,26 @@ def scaled_scoring(w, torch, binding):
                 bytes=nbytes, GBps=nbytes / ms / 1e6, frac_of_hbm_peak=nbytes / ms / 1e6 / PEAK_HBM_GBS)
 
 
+def axes_rerotation(w, step, torch, binding, b_bytes, reps):
+    """cs_kv_rerotate_axes (three-axis RoPE correction) on the step's own reuse plan: the window
+    slides in time only, so the shift is (delta, 0, 0); frequency pairs are mapped to (t, h, w) in
+    sections of 1/4, 3/8, 3/8 of the pairs (the 16/24/24 split of a 128-wide head).  Same bytes
+    as the one-dimensional call."""
+    half = w.head_dim // 2
+    n_t = half // 4
+    n_h = (half - n_t) // 2
+    axis = torch.cat([torch.zeros(n_t), torch.ones(n_h), torch.full((half - n_t - n_h,), 2.0)]).to(torch.uint8).cuda()
+    delta3 = torch.stack([step.delta, torch.zeros_like(step.delta), torch.zeros_like(step.delta)], dim=1).contiguous()
+    call = lambda: binding.cs_kv_rerotate_axes(
+        step.k_pool, step.v_pool, step.src_slot, step.dst_slot, delta3, axis, int(step.src_slot.shape[0]),
+        w.n_layers, w.n_kv_heads, w.head_dim, step.stride_layer, step.stride_slot, step.stride_head, w.rope_base,
+        binding.CS_ROPE_HALF_SPLIT, step.dtype)
+    call()
+    ms = event_time(torch, call, reps)
+    return dict(ms=ms, bytes=b_bytes, GBps=b_bytes / ms / 1e6, frac_of_hbm_peak=b_bytes / ms / 1e6 / PEAK_HBM_GBS,
+                sections=[n_t, n_h, half - n_t - n_h])
+
+
 def cpu_baseline(w, data, step, torch):
     """The oracle, as it stands, on the host: scoring, re-rotation of every reused row for all
     layers, then refresh write + attention for a bounded number of layers, scaled to all layers."""
@@ -310,6 +330,7 @@ def main():
         out["copy_calibration"] = copy_calibration(torch)
     if not args.no_scaled_scoring:
         out["score_compact_scaled"] = scaled_scoring(w, torch, binding)
+        out["kv_rerotate_axes"] = axes_rerotation(w, step, torch, binding, work["b_bytes"], reps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, data, step, torch)
     print(json.dumps(out))

@@ -149,6 +149,28 @@ int cs_kv_rerotate(void* k_cache, void* v_cache,
                    float rope_base, int32_t rope_style, int32_t dtype, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * (b') The same correction for multidimensional RoPE.       Paper Sec. 3.4.2 (after Eq. 6: "for
+ *     multidimensional RoPE, the correction follows the model's mapping from positional
+ *     components to rotary dimensions"); Sec. 4 names Qwen3-VL's three-axis mRoPE.
+ *
+ * A position is a triple (t, h, w).  Frequency pair i of a head (the same pairs and the same
+ * theta_i = rope_base^(-2i/head_dim) as in cs_kv_rerotate) is driven by positional component
+ * axis_of_pair[i], so row r rotates pair i by delta3[r][axis_of_pair[i]] * theta_i.  With every
+ * pair on one axis this is cs_kv_rerotate of that component.
+ *
+ *  delta3        in   int32 [n_rows][3]   (d_t, d_h, d_w) = p_new - p_old per component
+ *  axis_of_pair  in   uint8 [head_dim/2]  values 0, 1, 2 (a larger value is read as 2); device memory
+ * All other arguments, layouts, aliasing rules and errors as for cs_kv_rerotate; CS_EINVAL also
+ * when axis_of_pair is NULL.
+ * ------------------------------------------------------------------------------------------ */
+int cs_kv_rerotate_axes(void* k_cache, void* v_cache,
+                        const int32_t* src_slot, const int32_t* dst_slot, const int32_t* delta3,
+                        const uint8_t* axis_of_pair, int64_t n_rows,
+                        int32_t n_layers, int32_t n_kv_heads, int32_t head_dim,
+                        int64_t stride_layer, int64_t stride_slot, int64_t stride_head,
+                        float rope_base, int32_t rope_style, int32_t dtype, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * (c) In-place refresh write.                            Paper Sec. 3.5 ("newly computed K/V are
  *     written directly into the destination cache before causal attention is evaluated").
  *

@@ -27,7 +27,8 @@ _ERR = {CS_EINVAL: "CS_EINVAL", CS_EUNSUPPORTED: "CS_EUNSUPPORTED", CS_EHIP: "CS
         CS_EWORKSPACE: "CS_EWORKSPACE"}
 
 EXPORTS = ("cs_version", "cs_last_hip_error", "cs_score_compact_workspace", "cs_score_compact",
-           "cs_kv_rerotate", "cs_kv_refresh_scatter", "cs_window_prefill_attn_workspace",
+           "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
+           "cs_window_prefill_attn_workspace",
            "cs_window_prefill_attn")
 
 
@@ -64,6 +65,8 @@ def lib() -> ctypes.CDLL:
                                    vp, vp, vp, vp, sz, vp]
     L.cs_kv_rerotate.restype = c.c_int
     L.cs_kv_rerotate.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, i64, i64, f32, i32, i32, vp]
+    L.cs_kv_rerotate_axes.restype = c.c_int
+    L.cs_kv_rerotate_axes.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, i64, i64, f32, i32, i32, vp]
     L.cs_kv_refresh_scatter.restype = c.c_int
     L.cs_kv_refresh_scatter.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i64, i64, i32, vp]
     L.cs_window_prefill_attn_workspace.restype = sz
@@ -142,6 +145,17 @@ def cs_kv_rerotate(k_cache, v_cache, src_slot, dst_slot, delta, n_rows, n_layers
     _check("cs_kv_rerotate", lib().cs_kv_rerotate(
         _ptr(k_cache), _ptr(v_cache), _ptr(src_slot), _ptr(dst_slot), _ptr(delta), n_rows, n_layers,
         n_kv_heads, head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype,
+        _stream()))
+
+
+def cs_kv_rerotate_axes(k_cache, v_cache, src_slot, dst_slot, delta3, axis_of_pair, n_rows, n_layers, n_kv_heads,
+                        head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype):
+    fn = "cs_kv_rerotate_axes"
+    _need(fn, src_slot, n_rows, "src_slot"); _need(fn, dst_slot, n_rows, "dst_slot")
+    _need(fn, delta3, 3 * n_rows, "delta3"); _need(fn, axis_of_pair, head_dim // 2, "axis_of_pair")
+    _check(fn, lib().cs_kv_rerotate_axes(
+        _ptr(k_cache), _ptr(v_cache), _ptr(src_slot), _ptr(dst_slot), _ptr(delta3), _ptr(axis_of_pair), n_rows,
+        n_layers, n_kv_heads, head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype,
         _stream()))
 
 

@@ -15,6 +15,10 @@
 // double precision (a shift of a few thousand positions times theta_0 = 1 would lose 3 decimal
 // digits in float); sin/cos of the reduced angle (single-precision minimax polynomials with the
 // Cephes sinf/cosf coefficients), the products and the final rounding are single precision.
+//
+// Multidimensional RoPE (Sec. 3.4.2: "the correction follows the model's mapping from positional
+// components to rotary dimensions"): a row's shift is a triple (d_t, d_h, d_w) and frequency pair i
+// is driven by component axis_of_pair[i]; everything else is the same kernel (template flag).
 #include <math.h>
 
 #include "common.h"
@@ -29,7 +33,8 @@ struct RerotateParams {
   void* v;
   const int32_t* __restrict__ src_slot;
   const int32_t* __restrict__ dst_slot;  // nullptr: in place
-  const int32_t* __restrict__ delta;
+  const int32_t* __restrict__ delta;     // [n_rows], or [n_rows][3] with axis_of_pair
+  const uint8_t* __restrict__ axis_of_pair;   // [head_dim / 2] values 0..2, multi-axis kernels only
   int64_t n_rows;
   int64_t stride_layer, stride_slot, stride_head;
   int32_t n_layers, n_kv_heads, head_dim, style;
@@ -92,7 +97,7 @@ __device__ __forceinline__ void sincos_reduced(double ang, float* sn, float* cs_
   *cs_out = ((quad + 1) & 2) ? -c_q : c_q;
 }
 
-template <bool kBf16, int kStyle>
+template <bool kBf16, int kStyle, bool kAxes>
 __global__ __launch_bounds__(256) void rerotate_kernel(RerotateParams p) {
   using V = Vec<kBf16>;
   constexpr int E = V::kElems;           // pairs per thread = elements per vector
@@ -108,13 +113,25 @@ __global__ __launch_bounds__(256) void rerotate_kernel(RerotateParams p) {
 
   const int src = p.src_slot[row];
   const int dst = p.dst_slot ? p.dst_slot[row] : src;
-  const double dlt = static_cast<double>(p.delta[row]);
+  double dlt[3];
+  if (kAxes) {
+    dlt[0] = static_cast<double>(p.delta[row * 3]);
+    dlt[1] = static_cast<double>(p.delta[row * 3 + 1]);
+    dlt[2] = static_cast<double>(p.delta[row * 3 + 2]);
+  } else {
+    dlt[0] = dlt[1] = dlt[2] = static_cast<double>(p.delta[row]);
+  }
 
   float cs_[E], sn_[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const double theta = exp2(static_cast<double>(j * E + e) * p.neg_log2_base_2_over_d);
-    sincos_reduced(dlt * theta, &sn_[e], &cs_[e]);
+    double shift = dlt[0];
+    if (kAxes) {
+      const int axis = p.axis_of_pair[j * E + e];
+      shift = axis == 0 ? dlt[0] : axis == 1 ? dlt[1] : dlt[2];
+    }
+    sincos_reduced(shift * theta, &sn_[e], &cs_[e]);
   }
 
   // element offsets of the thread's two vectors inside a head
@@ -231,11 +248,13 @@ __global__ __launch_bounds__(256) void scatter_kernel(ScatterParams p) {
 
 }  // namespace
 
-extern "C" int cs_kv_rerotate(void* k_cache, void* v_cache, const int32_t* src_slot,
-                              const int32_t* dst_slot, const int32_t* delta, int64_t n_rows,
-                              int32_t n_layers, int32_t n_kv_heads, int32_t head_dim,
-                              int64_t stride_layer, int64_t stride_slot, int64_t stride_head,
-                              float rope_base, int32_t rope_style, int32_t dtype, void* stream) {
+namespace {
+
+// delta: [n_rows] shifts, or with axis_of_pair [n_rows][3] shifts per positional component.
+int rerotate_launch(void* k_cache, void* v_cache, const int32_t* src_slot, const int32_t* dst_slot,
+                    const int32_t* delta, const uint8_t* axis_of_pair, int64_t n_rows, int32_t n_layers,
+                    int32_t n_kv_heads, int32_t head_dim, int64_t stride_layer, int64_t stride_slot,
+                    int64_t stride_head, float rope_base, int32_t rope_style, int32_t dtype, void* stream) {
   if (n_rows < 0 || n_layers < 0 || n_kv_heads < 1 || head_dim < 1) return CS_EINVAL;
   if (stride_layer < 0 || stride_slot < 0 || stride_head < 0) return CS_EINVAL;
   if (!(rope_base > 0.0f)) return CS_EINVAL;
@@ -256,6 +275,7 @@ extern "C" int cs_kv_rerotate(void* k_cache, void* v_cache, const int32_t* src_s
   p.src_slot = src_slot;
   p.dst_slot = dst_slot;
   p.delta = delta;
+  p.axis_of_pair = axis_of_pair;
   p.n_rows = n_rows;
   p.stride_layer = stride_layer;
   p.stride_slot = stride_slot;
@@ -280,15 +300,45 @@ extern "C" int cs_kv_rerotate(void* k_cache, void* v_cache, const int32_t* src_s
   const dim3 grid(static_cast<unsigned>(blocks_x), static_cast<unsigned>((n_layers + lpb - 1) / lpb));
   hipStream_t st = cs::as_stream(stream);
   const bool half_split = rope_style == CS_ROPE_HALF_SPLIT;
-  if (dtype == CS_BF16 && half_split)
-    hipLaunchKernelGGL((rerotate_kernel<true, CS_ROPE_HALF_SPLIT>), grid, dim3(256), 0, st, p);
-  else if (dtype == CS_BF16)
-    hipLaunchKernelGGL((rerotate_kernel<true, CS_ROPE_INTERLEAVED>), grid, dim3(256), 0, st, p);
-  else if (half_split)
-    hipLaunchKernelGGL((rerotate_kernel<false, CS_ROPE_HALF_SPLIT>), grid, dim3(256), 0, st, p);
-  else
-    hipLaunchKernelGGL((rerotate_kernel<false, CS_ROPE_INTERLEAVED>), grid, dim3(256), 0, st, p);
+  const bool bf16 = dtype == CS_BF16;
+#define CS_LAUNCH_REROTATE(AXES)                                                                             \
+  do {                                                                                                       \
+    if (bf16 && half_split)                                                                                  \
+      hipLaunchKernelGGL((rerotate_kernel<true, CS_ROPE_HALF_SPLIT, AXES>), grid, dim3(256), 0, st, p);      \
+    else if (bf16)                                                                                           \
+      hipLaunchKernelGGL((rerotate_kernel<true, CS_ROPE_INTERLEAVED, AXES>), grid, dim3(256), 0, st, p);     \
+    else if (half_split)                                                                                     \
+      hipLaunchKernelGGL((rerotate_kernel<false, CS_ROPE_HALF_SPLIT, AXES>), grid, dim3(256), 0, st, p);     \
+    else                                                                                                     \
+      hipLaunchKernelGGL((rerotate_kernel<false, CS_ROPE_INTERLEAVED, AXES>), grid, dim3(256), 0, st, p);    \
+  } while (0)
+  if (axis_of_pair) CS_LAUNCH_REROTATE(true);
+  else CS_LAUNCH_REROTATE(false);
+#undef CS_LAUNCH_REROTATE
   return cs::note_hip(hipGetLastError());
+}
+
+}  // namespace
+
+extern "C" int cs_kv_rerotate(void* k_cache, void* v_cache, const int32_t* src_slot,
+                              const int32_t* dst_slot, const int32_t* delta, int64_t n_rows,
+                              int32_t n_layers, int32_t n_kv_heads, int32_t head_dim,
+                              int64_t stride_layer, int64_t stride_slot, int64_t stride_head,
+                              float rope_base, int32_t rope_style, int32_t dtype, void* stream) {
+  return rerotate_launch(k_cache, v_cache, src_slot, dst_slot, delta, nullptr, n_rows, n_layers, n_kv_heads,
+                         head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype, stream);
+}
+
+extern "C" int cs_kv_rerotate_axes(void* k_cache, void* v_cache, const int32_t* src_slot,
+                                   const int32_t* dst_slot, const int32_t* delta3,
+                                   const uint8_t* axis_of_pair, int64_t n_rows, int32_t n_layers,
+                                   int32_t n_kv_heads, int32_t head_dim, int64_t stride_layer,
+                                   int64_t stride_slot, int64_t stride_head, float rope_base,
+                                   int32_t rope_style, int32_t dtype, void* stream) {
+  if (n_rows > 0 && n_layers > 0 && !axis_of_pair) return CS_EINVAL;
+  return rerotate_launch(k_cache, v_cache, src_slot, dst_slot, delta3, axis_of_pair, n_rows, n_layers,
+                         n_kv_heads, head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style,
+                         dtype, stream);
 }
 
 extern "C" int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* slot,

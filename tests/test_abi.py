@@ -76,6 +76,10 @@ def test_host_side_argument_errors(lib):
     assert L.cs_kv_rerotate(one, one, one, z, one, 4, 1, 1, 64, 0, 64, 64, 0.0, 0, 1, z) == binding.CS_EINVAL
     assert L.cs_kv_rerotate(one, one, one, z, one, -1, 1, 1, 64, 0, 64, 64, 1e4, 0, 1, z) == binding.CS_EINVAL
     assert L.cs_kv_rerotate(one, one, one, z, one, 0, 1, 1, 64, 0, 64, 64, 1e4, 0, 1, z) == binding.CS_OK
+    # (b') the multi-axis form shares the checks and also needs its axis map
+    assert L.cs_kv_rerotate_axes(one, one, one, z, one, z, 4, 1, 1, 64, 0, 64, 64, 1e4, 0, 1, z) == binding.CS_EINVAL
+    assert L.cs_kv_rerotate_axes(one, one, one, z, one, one, 4, 1, 1, 72, 0, 72, 72, 1e4, 0, 1, z) == binding.CS_EUNSUPPORTED
+    assert L.cs_kv_rerotate_axes(one, one, one, z, one, one, 0, 1, 1, 64, 0, 64, 64, 1e4, 0, 1, z) == binding.CS_OK
     # (c)
     assert L.cs_kv_refresh_scatter(z, one, one, one, one, 4, 1, 64, 64, 64, 1, z) == binding.CS_EINVAL
     assert L.cs_kv_refresh_scatter(one, one, one, one, one, 4, 1, 60, 64, 64, 1, z) == binding.CS_EUNSUPPORTED

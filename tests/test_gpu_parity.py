@@ -227,6 +227,81 @@ def test_kv_rerotate_closed_form_on_gpu(cs):
     assert np.abs(hp.f64(cached.reshape(n, d)) - want).max() <= 2e-5
 
 
+# ------------------------------------------------------------------ (b') multi-axis correction
+def _sections_axis_map(sections, half, interleave=False):
+    """Frequency pairs -> axis: consecutive sections (Qwen2-VL style) or t/h/w interleaved."""
+    if interleave:
+        return (np.arange(half) % 3).astype(np.uint8)
+    m = np.concatenate([np.full(n, a, np.uint8) for a, n in enumerate(sections)])
+    assert m.size == half
+    return m
+
+
+AXES_CASES = [
+    # dtype, L, n_slots, Hkv, d, n_rows, style, repack, base, sections / interleave
+    ("f32", 2, 300, 2, 128, 97, 0, True, 1e6, [16, 24, 24]),
+    ("bf16", 28, 1024, 4, 128, 490, 0, True, 1e6, [16, 24, 24]),    # Qwen2-VL's sections, all layers
+    ("bf16", 5, 640, 8, 128, 333, 0, False, 1e6, "interleave"),      # axes interleaved over the pairs
+    ("bf16", 3, 400, 2, 64, 150, 1, True, 1e4, [8, 12, 12]),         # interleaved element pairs
+    ("bf16", 1, 64, 1, 16, 1, 0, True, 1e4, [2, 3, 3]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(AXES_CASES)))
+def test_kv_rerotate_axes(cs, case):
+    dtype, n_layers, n_slots, n_heads, d, n_rows, style, repack, base, sec = AXES_CASES[case]
+    say(f"kv_rerotate_axes case {case}: {dtype} L={n_layers} slots={n_slots} Hkv={n_heads} d={d} rows={n_rows} "
+        f"style={style} repack={repack} axes={sec}")
+    rng = np.random.default_rng(2500 + case)
+    axis = _sections_axis_map(sec, d // 2, interleave=(sec == "interleave"))
+    k = _pool(rng, (n_layers, n_slots, n_heads, d), dtype)
+    v = _pool(rng, (n_layers, n_slots, n_heads, d), dtype)
+    perm = rng.permutation(n_slots)
+    src = perm[:n_rows].astype(np.int32)
+    dst = perm[n_rows: 2 * n_rows].astype(np.int32) if repack else None
+    delta3 = np.stack([rng.integers(-2392, 2393, size=n_rows), rng.integers(-40, 41, size=n_rows),
+                       rng.integers(-40, 41, size=n_rows)], axis=1).astype(np.int32)
+    delta3[0] = [-256, 0, 0]                                     # the sliding window's own case: time only
+    k_ref, _ = oc.rerotate_axes(hp.f64(k), hp.f64(v), src, dst, delta3, axis, base, style)
+    kd, vd = k.to(DEV), v.to(DEV)
+    cs.cs_kv_rerotate_axes(kd, vd if repack else None, torch.from_numpy(src).to(DEV),
+                           torch.from_numpy(dst).to(DEV) if repack else None, torch.from_numpy(delta3).to(DEV),
+                           torch.from_numpy(axis).to(DEV), n_rows, n_layers, n_heads, d, kd.stride(0), kd.stride(1),
+                           kd.stride(2), base, style, cs.CS_BF16 if dtype == "bf16" else cs.CS_F32)
+    torch.cuda.synchronize()
+    k_out, v_out = kd.cpu(), vd.cpu()
+    tgt = dst if repack else src
+    got_rows = k_out[:, torch.from_numpy(tgt.astype(np.int64))].permute(1, 0, 2, 3).contiguous()
+    say(f"  -> {hp.check_rerotated(got_rows, k_ref, dtype)}")
+    if repack:
+        assert torch.equal(v_out[:, torch.from_numpy(dst.astype(np.int64))], v[:, torch.from_numpy(src.astype(np.int64))])
+    other = torch.from_numpy(np.setdiff1d(np.arange(n_slots), tgt))
+    assert torch.equal(k_out[:, other], k[:, other]) and torch.equal(v_out[:, other], v[:, other])
+    # row 0 shifted in time only: the pairs of the other two axes come back bit for bit
+    ia = np.arange(d // 2) if style == 0 else 2 * np.arange(d // 2)
+    ib = ia + d // 2 if style == 0 else ia + 1
+    still = torch.from_numpy(np.concatenate([ia[axis != 0], ib[axis != 0]]))
+    assert torch.equal(k_out[:, int(tgt[0])][..., still], k[:, int(src[0])][..., still])
+
+
+def test_kv_rerotate_axes_with_one_axis_equals_plain_call(cs):
+    say("kv_rerotate_axes: every pair on the time axis == cs_kv_rerotate, bit for bit")
+    rng = np.random.default_rng(77)
+    n_layers, n_slots, n_heads, d, n_rows = 4, 512, 4, 128, 200
+    k = _pool(rng, (n_layers, n_slots, n_heads, d), "bf16")
+    src = torch.from_numpy(rng.permutation(n_slots)[:n_rows].astype(np.int32)).to(DEV)
+    delta = rng.integers(-2392, 2393, size=n_rows).astype(np.int32)
+    delta3 = np.stack([delta, rng.integers(-9, 9, size=n_rows), rng.integers(-9, 9, size=n_rows)], 1).astype(np.int32)
+    a, b = k.to(DEV), k.to(DEV)
+    cs.cs_kv_rerotate(a, None, src, None, torch.from_numpy(delta).to(DEV), n_rows, n_layers, n_heads, d,
+                      a.stride(0), a.stride(1), a.stride(2), 1e6, 0, cs.CS_BF16)
+    cs.cs_kv_rerotate_axes(b, None, src, None, torch.from_numpy(delta3).to(DEV),
+                           torch.zeros(d // 2, dtype=torch.uint8, device=DEV), n_rows, n_layers, n_heads, d,
+                           b.stride(0), b.stride(1), b.stride(2), 1e6, 0, cs.CS_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(a.cpu(), b.cpu())
+
+
 # =============================================================================== (c) scatter
 @pytest.mark.parametrize("dtype,n_tok,n_heads,d,layout", [
     ("f32", 332, 1, 64, "shd"), ("bf16", 425, 4, 128, "shd"), ("bf16", 1000, 8, 128, "hsd"),
