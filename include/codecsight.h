@@ -119,6 +119,65 @@ int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intr
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * (p) Refresh plan on the device.     Paper Sec. 3.4.1 (overlap I-frames are anchors and are
+ *     recomputed, the other overlap frames reuse their cached K/V, new frames and the text
+ *     suffix are prefilled) and Sec. 3.5 (planning precedes KV-context preparation; a frame-aware
+ *     index maps visual-token spans to physical cache slots across cache-block boundaries).
+ *
+ * All n_streams windows advance by `stride` frames.  Per stream s the previous window held the
+ * kept visual tokens of its `window` frames in frame order, then n_text text tokens, entry j of
+ * that sequence in slot  block_table_old[s][j/16]*16 + j%16.  The new window is frames
+ * stride .. window-1 of the old one (the overlap) followed by the `stride` new frames, whose
+ * kept-token counts are kept_off[s*stride+f+1] - kept_off[s*stride+f] (cs_score_compact's
+ * output for a batch of `stride` frames per stream, stream-major), then the text; its entry j
+ * lives in slot  block_table_new[s][j/16]*16 + j%16.  Walking the new sequence in order:
+ *   token of an overlap frame that is not an I-frame -> one reused row: src_slot (its slot in the
+ *       old window), dst_slot (its slot in the new one), delta = -stride*tokens_per_frame
+ *       (positions are dense: frame slot * tokens_per_frame + token id);
+ *   token of an overlap I-frame (kind 0), of a new frame (kind 1), text token (kind 2)
+ *       -> one executed row: q_pos = j, q_slot = its new slot, q_kind.
+ * Reused rows of all streams are concatenated stream-major, and so are executed rows;
+ * cu_q[s] .. cu_q[s+1]-1 are stream s's executed rows, kv_len[s] the new sequence length.
+ * The lists are what cs_kv_rerotate (src_slot, dst_slot, delta), cs_kv_refresh_scatter (q_slot)
+ * and cs_window_prefill_attn (cu_q, q_pos, kv_len, block_table_new) take; nothing returns to
+ * the host.  Entries between a list's total and its capacity are padded (slots -1, which the
+ * consumers skip, delta 0, q_pos 0, q_kind 0xff), so the consumers can be called with the
+ * capacities as their row counts.
+ *
+ *  old_types, old_counts   in   uint8 / int32 [n_streams][window]   the cached window
+ *  new_types               in   uint8 [n_streams][stride]
+ *  kept_off                in   int32 [n_streams*stride + 1]
+ *  block_table_old / _new  in   int32 [n_streams][max_blocks_old / _new]
+ *  src_slot, dst_slot, delta    out  int32 [reuse_cap]
+ *  q_pos, q_slot, q_kind        out  int32, int32, uint8 [q_cap]
+ *  cu_q  out int32 [n_streams+1];  kv_len  out int32 [n_streams]
+ *  out_types, out_counts   out  uint8 / int32 [n_streams][window]: the new window, the next
+ *                          step's old_types / old_counts (must not alias them)
+ *  totals                  out  int32 [4]: reused rows, executed rows, flags (1: reused rows exceed
+ *                          reuse_cap, 2: executed rows exceed q_cap, 4: a sequence index falls
+ *                          outside its block-table row), 0.  Rows beyond a capacity are not
+ *                          written; a row whose slot cannot be formed gets slot -1.
+ *  workspace               cs_plan_refresh_workspace() bytes, 16-byte aligned, contents need not
+ *                          be initialised
+ * All pointers are device memory.  Bit exact (integer work).
+ * Errors: CS_EINVAL (null pointer, negative size, window < 1, stride outside 1..window,
+ *         tokens_per_frame < 1), CS_EUNSUPPORTED (n_streams*(window+1), a capacity or
+ *         stride*tokens_per_frame >= 2^31), CS_EWORKSPACE, CS_EHIP.
+ * ------------------------------------------------------------------------------------------ */
+size_t cs_plan_refresh_workspace(int32_t n_streams, int32_t window);
+
+int cs_plan_refresh(const uint8_t* old_types, const int32_t* old_counts,
+                    const uint8_t* new_types, const int32_t* kept_off,
+                    const int32_t* block_table_old, int32_t max_blocks_old,
+                    const int32_t* block_table_new, int32_t max_blocks_new,
+                    int32_t n_streams, int32_t window, int32_t stride, int32_t n_text,
+                    int32_t tokens_per_frame, int64_t reuse_cap, int64_t q_cap,
+                    int32_t* src_slot, int32_t* dst_slot, int32_t* delta,
+                    int32_t* q_pos, int32_t* q_slot, uint8_t* q_kind,
+                    int32_t* cu_q, int32_t* kv_len, uint8_t* out_types, int32_t* out_counts,
+                    int32_t* totals, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * (b) Position-corrected reuse of cached keys.          Paper Sec. 3.4.2, Eq. 6; Sec. 3.5
  *     ("repacking reusable states into the destination KV cache").
  *
@@ -136,7 +195,8 @@ int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intr
  *
  *  k_cache, v_cache  i/o  pool of all layers: element (l, slot, h, c) at
  *                         l*stride_layer + slot*stride_slot + h*stride_head + c; 16-byte aligned
- *  src_slot, delta   in   int32 [n_rows];   dst_slot in int32 [n_rows] or NULL
+ *  src_slot, delta   in   int32 [n_rows];   dst_slot in int32 [n_rows] or NULL; a row with a
+ *                         negative src_slot or dst_slot is skipped
  * Errors: CS_EINVAL (null k_cache/src_slot/delta, v_cache NULL with dst_slot given, negative
  *         sizes, rope_base <= 0), CS_EUNSUPPORTED (head_dim not a multiple of 16 or > 256,
  *         strides not multiples of 16 bytes, unknown dtype / rope_style), CS_EHIP.
@@ -204,7 +264,9 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  * result.  CS_F32: fp32 throughout.
  *
  *  q, out        [n_q][n_q_heads][head_dim] contiguous, 16-byte aligned
- *  cu_q          int32 [n_streams+1], cu_q[0] = 0, cu_q[n_streams] = n_q
+ *  cu_q          int32 [n_streams+1], cu_q[0] = 0, cu_q[n_streams] <= n_q: n_q sizes the launch
+ *                and may be an upper bound (rows from cu_q[n_streams] on are neither read nor
+ *                written), so that a plan made on the device needs no host copy of its totals
  *  q_pos         int32 [n_q];  kv_len int32 [n_streams]: q_pos < kv_len, and block_table row s
  *                defines entries 0 .. ceil(kv_len[s]/16)-1
  *  block_table   int32 [n_streams][max_blocks]

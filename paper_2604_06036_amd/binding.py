@@ -27,7 +27,7 @@ _ERR = {CS_EINVAL: "CS_EINVAL", CS_EUNSUPPORTED: "CS_EUNSUPPORTED", CS_EHIP: "CS
         CS_EWORKSPACE: "CS_EWORKSPACE"}
 
 EXPORTS = ("cs_version", "cs_last_hip_error", "cs_score_compact_workspace", "cs_score_compact",
-           "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
+           "cs_plan_refresh_workspace", "cs_plan_refresh", "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
            "cs_window_prefill_attn_workspace",
            "cs_window_prefill_attn")
 
@@ -63,6 +63,11 @@ def lib() -> ctypes.CDLL:
     L.cs_score_compact.restype = c.c_int
     L.cs_score_compact.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, u32, u32, i32,
                                    vp, vp, vp, vp, sz, vp]
+    L.cs_plan_refresh_workspace.restype = sz
+    L.cs_plan_refresh_workspace.argtypes = [i32, i32]
+    L.cs_plan_refresh.restype = c.c_int
+    L.cs_plan_refresh.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, i64, i64,
+                                  vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cs_kv_rerotate.restype = c.c_int
     L.cs_kv_rerotate.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, i64, i64, f32, i32, i32, vp]
     L.cs_kv_rerotate_axes.restype = c.c_int
@@ -145,6 +150,37 @@ def cs_kv_rerotate(k_cache, v_cache, src_slot, dst_slot, delta, n_rows, n_layers
     _check("cs_kv_rerotate", lib().cs_kv_rerotate(
         _ptr(k_cache), _ptr(v_cache), _ptr(src_slot), _ptr(dst_slot), _ptr(delta), n_rows, n_layers,
         n_kv_heads, head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype,
+        _stream()))
+
+
+def cs_plan_refresh_workspace(n_streams, window) -> int:
+    return int(lib().cs_plan_refresh_workspace(n_streams, window))
+
+
+def cs_plan_refresh(old_types, old_counts, new_types, kept_off, block_table_old, max_blocks_old,
+                    block_table_new, max_blocks_new, n_streams, window, stride, n_text, tokens_per_frame,
+                    reuse_cap, q_cap, src_slot, dst_slot, delta, q_pos, q_slot, q_kind, cu_q, kv_len,
+                    out_types, out_counts, totals, workspace, workspace_bytes=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = "cs_plan_refresh"
+    if n_streams > 0 and window > 0 and 0 < stride <= window:
+        _need(fn, old_types, n_streams * window, "old_types"); _need(fn, old_counts, n_streams * window, "old_counts")
+        _need(fn, new_types, n_streams * stride, "new_types"); _need(fn, kept_off, n_streams * stride + 1, "kept_off")
+        _need(fn, block_table_old, n_streams * max_blocks_old, "block_table_old")
+        _need(fn, block_table_new, n_streams * max_blocks_new, "block_table_new")
+        _need(fn, out_types, n_streams * window, "out_types"); _need(fn, out_counts, n_streams * window, "out_counts")
+        _need(fn, cu_q, n_streams + 1, "cu_q"); _need(fn, kv_len, n_streams, "kv_len")
+    for t, what in ((src_slot, "src_slot"), (dst_slot, "dst_slot"), (delta, "delta")):
+        _need(fn, t, reuse_cap, what)
+    for t, what in ((q_pos, "q_pos"), (q_slot, "q_slot"), (q_kind, "q_kind")):
+        _need(fn, t, q_cap, what)
+    _need(fn, totals, 4, "totals")
+    _check(fn, lib().cs_plan_refresh(
+        _ptr(old_types), _ptr(old_counts), _ptr(new_types), _ptr(kept_off), _ptr(block_table_old), max_blocks_old,
+        _ptr(block_table_new), max_blocks_new, n_streams, window, stride, n_text, tokens_per_frame, reuse_cap,
+        q_cap, _ptr(src_slot), _ptr(dst_slot), _ptr(delta), _ptr(q_pos), _ptr(q_slot), _ptr(q_kind), _ptr(cu_q),
+        _ptr(kv_len), _ptr(out_types), _ptr(out_counts), _ptr(totals), _ptr(workspace), workspace_bytes,
         _stream()))
 
 

@@ -113,6 +113,7 @@ __global__ __launch_bounds__(256) void rerotate_kernel(RerotateParams p) {
 
   const int src = p.src_slot[row];
   const int dst = p.dst_slot ? p.dst_slot[row] : src;
+  if (src < 0 || dst < 0) return;        // padding rows of a list sized to its capacity
   double dlt[3];
   if (kAxes) {
     dlt[0] = static_cast<double>(p.delta[row * 3]);

@@ -1196,6 +1196,7 @@ __global__ __launch_bounds__(256) void window_attn_f32_kernel(AttnParams p) {
   const int64_t unit = static_cast<int64_t>(blockIdx.x) * 4 + wave;      // (query, head)
   if (unit >= p.n_q * p.n_q_heads) return;
   const int tok = static_cast<int>(unit / p.n_q_heads);
+  if (tok >= p.cu_q[p.n_streams]) return;               // n_q may be an upper bound
   const int head = static_cast<int>(unit - static_cast<int64_t>(tok) * p.n_q_heads);
   const int kvh = head / p.group;
   int s = 0;

@@ -229,3 +229,68 @@ class DeviceStep:
         for layer in range(self.data.workload.n_layers):
             self.refresh_scatter(layer)
             self.attention(layer, reuse_plan=layer > 0)
+
+
+class DevicePlannedStep(DeviceStep):
+    """The same step with the refresh plan made on the GPU (cs_plan_refresh) from the offsets the
+    scoring call leaves in device memory: no list, count or offset passes through the host between
+    the calls.  The row lists are sized to capacities the caller budgets (`reuse_cap`, `q_cap`);
+    the consumers are launched over the capacities and skip the padding."""
+
+    def __init__(self, data: StepData, reuse_cap: Optional[int] = None, q_cap: Optional[int] = None):
+        super().__init__(data)
+        import torch
+        cs, dev, w, p = self.cs, self.dev, data.workload, data.plan
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        n_reuse, n_q = int(p.src_slot.shape[0]), int(p.q_pos.shape[0])
+        self.reuse_cap = n_reuse if reuse_cap is None else int(reuse_cap)
+        self.q_cap = n_q if q_cap is None else int(q_cap)
+        if self.q_cap < n_q or self.reuse_cap < n_reuse:
+            raise ValueError("capacities below the step's row counts")
+        old = data.old_layout
+        self.old_types, self.old_counts = to(old.frame_type), to(old.counts)
+        self.bt_old = to(old.block_table)
+        self.max_blocks_old = int(old.block_table.shape[1])
+        i32 = lambda n, fill: torch.full((max(1, n),), fill, dtype=torch.int32, device=dev)
+        # the host plan's lists are dropped: everything below is written by the device planner
+        self.src_slot, self.dst_slot, self.delta = (i32(self.reuse_cap, -9) for _ in range(3))
+        self.q_pos, self.q_slot = i32(self.q_cap, -9), i32(self.q_cap, -9)
+        self.q_kind = torch.full((max(1, self.q_cap),), 7, dtype=torch.uint8, device=dev)
+        self.cu_q, self.kv_len = i32(w.n_streams + 1, -9), i32(w.n_streams, -9)
+        self.new_types_out = torch.zeros_like(self.old_types)
+        self.new_counts_out = torch.zeros_like(self.old_counts)
+        self.totals = i32(4, -9)
+        self.ws_p_bytes = cs.cs_plan_refresh_workspace(w.n_streams, w.window)
+        self.ws_p = torch.zeros((max(8, self.ws_p_bytes),), dtype=torch.uint8, device=dev)
+        if self.q_cap != n_q:
+            grow = lambda t: torch.cat([t, torch.zeros((t.shape[0], self.q_cap - n_q) + tuple(t.shape[2:]),
+                                                       dtype=t.dtype, device=dev)], dim=1)
+            self.q, self.k_new, self.v_new = grow(self.q), grow(self.k_new), grow(self.v_new)
+            self.out = torch.zeros_like(self.q)
+            self.ws_d_bytes = cs.cs_window_prefill_attn_workspace(self.q_cap, w.n_streams, w.n_q_heads,
+                                                                  w.n_kv_heads, w.head_dim, self.max_blocks,
+                                                                  self.dtype)
+            self.ws_d = torch.zeros((max(8, self.ws_d_bytes),), dtype=torch.uint8, device=dev)
+        self.n_rows_true, self.n_q_true = n_reuse, n_q
+        self.n_q = self.q_cap
+
+    def plan_refresh(self):
+        w = self.data.workload
+        self.cs.cs_plan_refresh(self.old_types, self.old_counts, self.frame_type, self.kept_off, self.bt_old,
+                                self.max_blocks_old, self.block_table, self.max_blocks, w.n_streams, w.window,
+                                w.stride, w.n_text, w.tokens_per_frame, self.reuse_cap, self.q_cap,
+                                self.src_slot, self.dst_slot, self.delta, self.q_pos, self.q_slot, self.q_kind,
+                                self.cu_q, self.kv_len, self.new_types_out, self.new_counts_out, self.totals,
+                                self.ws_p, self.ws_p_bytes)
+
+    def rerotate(self, in_place: bool = False):
+        if self.reuse_cap > 0:
+            super().rerotate(in_place)
+
+    def run(self):
+        self.score_compact()
+        self.plan_refresh()
+        self.rerotate()
+        for layer in range(self.data.workload.n_layers):
+            self.refresh_scatter(layer)
+            self.attention(layer, reuse_plan=layer > 0)

@@ -66,6 +66,38 @@ def test_host_side_argument_errors(lib):
     assert L.cs_score_compact(z, z, z, one, one, z, 1, 1, 16, 16, 1, 0, 0, 0, one, one, one, one, 64, z) == binding.CS_EINVAL
     assert L.cs_score_compact(one, z, z, one, one, z, 1, 1, 16, 16, 1, 0, 0, 0, one, one, one, z, 0, z) == binding.CS_EWORKSPACE
     assert L.cs_score_compact(one, z, z, one, one, z, 8, 8, 16, 16, 1, 0, 0, 0, one, one, one, one, 8, z) == binding.CS_EWORKSPACE
+    # (p) the device planner
+    def plan(**kw):
+        a = dict(ot=one, oc=one, nt=one, ko=one, bto=one, mbo=4, btn=one, mbn=4, ns=2, w=8, s=1, nt_=16, t=64,
+                 rc=100, qc=100, src=one, dst=one, dl=one, qp=one, qs=one, qk=one, cu=one, kvl=one, oty=one,
+                 ocn=one, tot=one, ws=one, wsb=1 << 20)
+        a.update(kw)
+        return L.cs_plan_refresh(a["ot"], a["oc"], a["nt"], a["ko"], a["bto"], a["mbo"], a["btn"], a["mbn"],
+                                 a["ns"], a["w"], a["s"], a["nt_"], a["t"], a["rc"], a["qc"], a["src"], a["dst"],
+                                 a["dl"], a["qp"], a["qs"], a["qk"], a["cu"], a["kvl"], a["oty"], a["ocn"],
+                                 a["tot"], a["ws"], a["wsb"], z)
+    assert plan(ns=-1) == binding.CS_EINVAL
+    assert plan(w=0) == binding.CS_EINVAL
+    assert plan(s=0) == binding.CS_EINVAL
+    assert plan(s=9) == binding.CS_EINVAL
+    assert plan(t=0) == binding.CS_EINVAL
+    assert plan(nt_=-1) == binding.CS_EINVAL
+    assert plan(rc=-1) == binding.CS_EINVAL
+    assert plan(ot=z) == binding.CS_EINVAL
+    assert plan(ko=z) == binding.CS_EINVAL
+    assert plan(src=z) == binding.CS_EINVAL
+    assert plan(qk=z) == binding.CS_EINVAL
+    assert plan(tot=z) == binding.CS_EINVAL
+    assert plan(cu=z) == binding.CS_EINVAL
+    assert plan(rc=1 << 31) == binding.CS_EUNSUPPORTED
+    assert plan(ns=1 << 20, w=1 << 11) == binding.CS_EUNSUPPORTED
+    assert plan(s=8, t=1 << 28) == binding.CS_EUNSUPPORTED
+    need = L.cs_plan_refresh_workspace(2, 8)
+    assert need >= 2 * 9 * 16 + 4 * 2 * 4 and need % 256 == 0
+    assert L.cs_plan_refresh_workspace(0, 8) == 0 and L.cs_plan_refresh_workspace(2, 0) == 0
+    assert plan(ws=z, wsb=0) == binding.CS_EWORKSPACE
+    assert plan(wsb=need - 1) == binding.CS_EWORKSPACE
+    assert plan(ws=ctypes.c_void_p(24), wsb=need) == binding.CS_EWORKSPACE
     # (b)
     assert L.cs_kv_rerotate(z, z, one, z, one, 4, 1, 1, 64, 0, 64, 64, 1e4, 0, 1, z) == binding.CS_EINVAL
     assert L.cs_kv_rerotate(one, z, one, one, one, 4, 1, 1, 64, 0, 64, 64, 1e4, 0, 1, z) == binding.CS_EINVAL

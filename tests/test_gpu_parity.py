@@ -492,6 +492,178 @@ def test_attention_properties_on_gpu(cs):
         assert torch.equal(out[0, h], vr[0, h // (hq // hkv)])
 
 
+# =============================================================================== (p) refresh plan
+def _plan_inputs(rng, n_streams, window, stride, t_per, n_text, p_iframe, p_empty, shuffle=True):
+    """Random cached windows + new frames: counts in 0..T (some frames empty), I-frames anywhere."""
+    def counts(n):
+        c = rng.integers(0, t_per + 1, size=(n_streams, n)).astype(np.int32)
+        c[rng.random((n_streams, n)) < p_empty] = 0
+        return c
+    old_types = (rng.random((n_streams, window)) < p_iframe).astype(np.uint8)
+    new_types = (rng.random((n_streams, stride)) < p_iframe).astype(np.uint8)
+    old_counts, new_counts = counts(window), counts(stride)
+    old_len = old_counts.sum(1) + n_text
+    new_len = old_counts[:, stride:].sum(1) + new_counts.sum(1) + n_text
+    nb_old, nb_new = (old_len + 15) // 16, (new_len + 15) // 16
+    mb_old, mb_new = max(1, int(nb_old.max(initial=0))), max(1, int(nb_new.max(initial=0)))
+    total = int(nb_old.sum() + nb_new.sum())
+    ids = rng.permutation(total + 5) if shuffle else np.arange(total + 5)
+    bt_old = np.full((n_streams, mb_old), -3, np.int32)
+    bt_new = np.full((n_streams, mb_new), -3, np.int32)
+    at = 0
+    for s in range(n_streams):
+        bt_old[s, : nb_old[s]] = ids[at: at + nb_old[s]]; at += int(nb_old[s])
+        bt_new[s, : nb_new[s]] = ids[at: at + nb_new[s]]; at += int(nb_new[s])
+    return old_types, old_counts, new_types, new_counts, bt_old, bt_new
+
+
+def _plan_oracle(old_types, old_counts, new_types, new_counts, bt_old, bt_new, n_text, t_per):
+    from oracle import plan_oracle as po
+    keys = ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "q_kind")
+    cat = {k: [] for k in keys}
+    cu_q, kv_len = [0], []
+    for s in range(old_types.shape[0]):
+        pl = po.plan_stream(old_types[s].tolist(), old_counts[s].tolist(), new_types[s].tolist(),
+                            new_counts[s].tolist(), n_text, t_per, bt_old[s], bt_new[s])
+        for k in keys:
+            cat[k] += pl[k]
+        cu_q.append(cu_q[-1] + len(pl["q_pos"]))
+        kv_len.append(pl["kv_len"])
+    out = {k: np.asarray(v, np.int64) for k, v in cat.items()}
+    out["cu_q"], out["kv_len"] = np.asarray(cu_q, np.int64), np.asarray(kv_len, np.int64)
+    return out
+
+
+def _plan_gpu(cs, old_types, old_counts, new_types, new_counts, bt_old, bt_new, n_text, t_per, reuse_cap, q_cap):
+    n_streams, window = old_types.shape
+    stride = new_types.shape[1]
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    kept_off = np.concatenate([[0], np.cumsum(new_counts.reshape(-1))]).astype(np.int32) + 11   # any base
+    fill = lambda n, v, dt=torch.int32: torch.full((max(1, n),), v, dtype=dt, device=DEV)
+    o = dict(src_slot=fill(reuse_cap + 3, -77), dst_slot=fill(reuse_cap + 3, -77), delta=fill(reuse_cap + 3, -77),
+             q_pos=fill(q_cap + 3, -77), q_slot=fill(q_cap + 3, -77), q_kind=fill(q_cap + 3, 99, torch.uint8),
+             cu_q=fill(n_streams + 1, -77), kv_len=fill(n_streams, -77),
+             out_types=fill(n_streams * window, 99, torch.uint8), out_counts=fill(n_streams * window, -77),
+             totals=fill(4, -77))
+    nbytes = cs.cs_plan_refresh_workspace(n_streams, window)
+    ws = torch.randint(0, 255, (max(16, nbytes),), dtype=torch.uint8, device=DEV)           # dirty workspace
+    cs.cs_plan_refresh(d(old_types), d(old_counts), d(new_types), d(kept_off), d(bt_old), bt_old.shape[1],
+                       d(bt_new), bt_new.shape[1], n_streams, window, stride, n_text, t_per, reuse_cap, q_cap,
+                       o["src_slot"], o["dst_slot"], o["delta"], o["q_pos"], o["q_slot"], o["q_kind"], o["cu_q"],
+                       o["kv_len"], o["out_types"], o["out_counts"], o["totals"], ws if nbytes else None, nbytes)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in o.items()}
+
+
+def _check_plan(got, want, old_types, old_counts, new_types, new_counts, reuse_cap, q_cap, flags=0):
+    n_streams, window = old_types.shape
+    stride = new_types.shape[1]
+    n_reuse, n_q = int(want["src_slot"].size), int(want["q_pos"].size)
+    assert got["totals"].tolist() == [n_reuse, n_q, flags, 0]
+    assert np.array_equal(got["cu_q"], want["cu_q"])
+    assert np.array_equal(got["kv_len"][:n_streams], want["kv_len"])
+    r, q = min(n_reuse, reuse_cap), min(n_q, q_cap)
+    for k in ("src_slot", "dst_slot", "delta"):
+        assert np.array_equal(got[k][:r], want[k][:r]), k
+        assert np.all(got[k][r:reuse_cap] == (0 if k == "delta" else -1)), k          # padding
+        assert np.all(got[k][reuse_cap:] == -77), k                                    # past the capacity: untouched
+    for k in ("q_pos", "q_slot", "q_kind"):
+        assert np.array_equal(got[k][:q], want[k][:q]), k
+        assert np.all(got[k][q:q_cap] == {"q_pos": 0, "q_slot": -1, "q_kind": 255}[k]), k
+        assert np.all(got[k][q_cap:] == (99 if k == "q_kind" else -77)), k
+    if n_streams:
+        types = np.concatenate([old_types[:, stride:], new_types], axis=1)
+        counts = np.concatenate([old_counts[:, stride:], new_counts], axis=1)
+        assert np.array_equal(got["out_types"].reshape(n_streams, window), types)
+        assert np.array_equal(got["out_counts"].reshape(n_streams, window), counts)
+
+
+PLAN_CASES = [
+    # streams, window, stride, T, n_text, p_iframe, p_empty, slack
+    (1, 4, 1, 16, 4, 0.3, 0.0, 0),
+    (3, 8, 1, 256, 64, 0.15, 0.1, 0),
+    (5, 8, 2, 64, 0, 0.2, 0.3, 7),
+    (2, 16, 16, 40, 9, 0.2, 0.0, 300),           # stride = window: nothing overlaps, nothing reused
+    (4, 70, 3, 19, 5, 0.1, 0.2, 1),              # more than 64 frames: the per-stream scan carries across chunks
+    (2, 200, 130, 7, 1, 0.5, 0.1, 0),            # more than 64 departing frames
+    (1100, 3, 1, 5, 2, 0.3, 0.3, 513),           # more than 1024 streams: the stream scan carries across chunks
+    (64, 8, 1, 256, 32, 0.125, 0.0, 256),
+    (7, 6, 2, 33, 3, 1.0, 0.0, 0),               # every overlap frame an anchor: no reused row
+    (7, 6, 2, 33, 3, 0.0, 0.0, 0),               # no anchor
+    (3, 5, 2, 12, 0, 0.3, 1.0, 4),               # every frame empty, no text: no rows at all
+]
+
+
+@pytest.mark.parametrize("case", range(len(PLAN_CASES)))
+def test_plan_refresh(cs, case):
+    """Every list of the device plan equals the oracle's, bit for bit; padding and totals as declared."""
+    n_streams, window, stride, t_per, n_text, p_i, p_e, slack = PLAN_CASES[case]
+    say(f"plan_refresh case {case}: streams={n_streams} W={window} S={stride} T={t_per} text={n_text}")
+    rng = np.random.default_rng(7000 + case)
+    ins = _plan_inputs(rng, n_streams, window, stride, t_per, n_text, p_i, p_e)
+    want = _plan_oracle(*ins, n_text, t_per)
+    reuse_cap, q_cap = int(want["src_slot"].size) + slack, int(want["q_pos"].size) + slack
+    got = _plan_gpu(cs, *ins, n_text, t_per, reuse_cap, q_cap)
+    _check_plan(got, want, *ins[:4], reuse_cap, q_cap)
+    say(f"  reused rows {want['src_slot'].size}, executed rows {want['q_pos'].size}")
+
+
+def test_plan_refresh_no_streams(cs):
+    say("plan_refresh with an empty batch")
+    z8, z32 = np.zeros((0, 4), np.uint8), np.zeros((0, 4), np.int32)
+    got = _plan_gpu(cs, z8, z32, np.zeros((0, 1), np.uint8), np.zeros((0, 1), np.int32), np.zeros((0, 1), np.int32),
+                    np.zeros((0, 1), np.int32), 4, 16, 5, 6)
+    assert got["totals"].tolist() == [0, 0, 0, 0] and got["cu_q"][0] == 0
+    assert np.all(got["src_slot"][:5] == -1) and np.all(got["q_slot"][:6] == -1)
+
+
+def test_plan_refresh_reports_what_does_not_fit(cs):
+    """Capacities or block-table rows that are too short raise flags; nothing is written outside
+    the capacities and no slot is formed from a missing block-table entry."""
+    say("plan_refresh: capacities and block tables too small")
+    rng = np.random.default_rng(7100)
+    n_text, t_per = 8, 32
+    ins = _plan_inputs(rng, 6, 8, 1, t_per, n_text, 0.15, 0.0)
+    want = _plan_oracle(*ins, n_text, t_per)
+    n_reuse, n_q = int(want["src_slot"].size), int(want["q_pos"].size)
+    got = _plan_gpu(cs, *ins, n_text, t_per, n_reuse - 10, n_q)
+    _check_plan(got, want, *ins[:4], n_reuse - 10, n_q, flags=1)
+    got = _plan_gpu(cs, *ins, n_text, t_per, n_reuse, n_q // 2)
+    _check_plan(got, want, *ins[:4], n_reuse, n_q // 2, flags=2)
+    got = _plan_gpu(cs, *ins, n_text, t_per, 0, 0)
+    _check_plan(got, want, *ins[:4], 0, 0, flags=3)
+    # the new block-table rows cut to two blocks: indices from 32 on have no slot
+    old_types, old_counts, new_types, new_counts, bt_old, bt_new = ins
+    got = _plan_gpu(cs, old_types, old_counts, new_types, new_counts, bt_old, bt_new[:, :2].copy(), n_text, t_per,
+                    n_reuse, n_q)
+    assert got["totals"].tolist() == [n_reuse, n_q, 4, 0]
+    lost_q = want["q_pos"] >= 32
+    assert np.array_equal(got["q_pos"][:n_q], want["q_pos"])
+    assert np.all(got["q_slot"][:n_q][lost_q] == -1)
+    assert np.array_equal(got["q_slot"][:n_q][~lost_q], want["q_slot"][~lost_q])
+    lost_r = got["dst_slot"][:n_reuse] < 0
+    assert lost_r.any() and np.all(got["src_slot"][:n_reuse][lost_r] == -1)
+    assert np.array_equal(got["src_slot"][:n_reuse][~lost_r], want["src_slot"][~lost_r])
+    assert np.array_equal(got["dst_slot"][:n_reuse][~lost_r], want["dst_slot"][~lost_r])
+
+
+def test_plan_refresh_matches_the_host_planner_on_a_workload(cs):
+    """The product's own host planner and the device planner agree on a workload-shaped batch."""
+    w = synth.small_variant(synth.CFG4, n_streams=16)
+    say(f"plan_refresh vs host planner: {w.name}")
+    data = engine.assemble_step(w, engine.hip_scorer, device="cpu", with_tensors=False)
+    p, old = data.plan, data.old_layout
+    new_counts = p.layout.counts[:, w.window - w.stride:]
+    new_types = p.layout.frame_type[:, w.window - w.stride:]
+    got = _plan_gpu(cs, old.frame_type, old.counts, new_types, new_counts, old.block_table, p.layout.block_table,
+                    w.n_text, w.tokens_per_frame, p.src_slot.size + 100, p.q_pos.size + 100)
+    for k in ("src_slot", "dst_slot", "delta"):
+        assert np.array_equal(got[k][: p.src_slot.size], getattr(p, k)), k
+    for k in ("q_pos", "q_slot", "q_kind"):
+        assert np.array_equal(got[k][: p.q_pos.size], getattr(p, k)), k
+    assert np.array_equal(got["cu_q"], p.cu_q) and np.array_equal(got["kv_len"], p.kv_len)
+
+
 # =============================================================================== whole step
 def _oracle_step(data_o: engine.StepData, layers):
     """b -> c -> d with oracle pieces on host copies of the inputs; returns per-layer results."""
@@ -555,6 +727,37 @@ def test_whole_step_against_oracle(cs, wi):
     assert torch.equal(step.v_pool.cpu(), v_pool_o)
     for layer in layers:
         say(f"  attention layer {layer}: {hp.check_attention(step.out[layer].cpu(), outs[layer], w.dtype)}")
+
+
+@pytest.mark.parametrize("wi,slack", [(0, 0), (1, 0), (1, 300), (2, 1000), (3, 77)])
+def test_device_planned_step_equals_host_planned_step(cs, wi, slack):
+    """score -> plan on the device -> re-rotate -> refresh write -> attention with nothing passing
+    through the host, lists padded to capacities: the cache ends bit-equal to the host-planned
+    step's (itself checked against the oracle above) and attention agrees (bit-equal when the
+    capacities equal the row counts, since then the launches are identical)."""
+    w = STEP_WORKLOADS[wi]
+    say(f"device-planned step: {w.name} streams={w.n_streams} layers={w.n_layers} slack={slack}")
+    data = engine.assemble_step(w, engine.hip_scorer, device="cpu")
+    host = engine.DeviceStep(data)
+    host.run()
+    n_reuse, n_q = data.info["n_reuse"], data.info["n_q"]
+    devp = engine.DevicePlannedStep(data, reuse_cap=n_reuse + slack, q_cap=n_q + slack)
+    devp.run()
+    torch.cuda.synchronize()
+    assert devp.totals.cpu().tolist() == [n_reuse, n_q, 0, 0]
+    for name in ("src_slot", "dst_slot", "delta"):
+        assert torch.equal(getattr(devp, name)[:n_reuse], getattr(host, name)), name
+    for name in ("q_pos", "q_slot"):
+        assert torch.equal(getattr(devp, name)[:n_q], getattr(host, name)), name
+    assert torch.equal(devp.cu_q, host.cu_q) and torch.equal(devp.kv_len, host.kv_len)
+    assert torch.equal(devp.k_pool.view(torch.uint8), host.k_pool.view(torch.uint8))
+    assert torch.equal(devp.v_pool.view(torch.uint8), host.v_pool.view(torch.uint8))
+    a, b = devp.out[:, :n_q].float().cpu(), host.out.float().cpu()
+    if slack == 0:
+        assert torch.equal(a, b)
+    else:
+        assert float((a - b).abs().max()) <= (2e-2 if w.dtype == "bf16" else 1e-4)
+    assert not devp.out[:, n_q:].any()                           # rows past the executed rows are not written
 
 
 FULL_WORKLOADS = [synth.CFG1, synth.CFG2, synth.CFG3P, synth.CFG3D, synth.CFG4]
