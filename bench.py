@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM counters and copy bandwidth)")
+    ap.add_argument("--no-device-plan", action="store_true",
+                    help="skip the leg that runs the step with the refresh plan made on the GPU")
     ap.add_argument("--no-scaled-scoring", action="store_true",
                     help="skip the scaled-batch bandwidth measurement of cs_score_compact")
     return ap.parse_args()
@@ -143,6 +145,57 @@ def axes_rerotation(w, step, torch, binding, b_bytes, reps):
     ms = event_time(torch, call, reps)
     return dict(ms=ms, bytes=b_bytes, GBps=b_bytes / ms / 1e6, frac_of_hbm_peak=b_bytes / ms / 1e6 / PEAK_HBM_GBS,
                 sections=[n_t, n_h, half - n_t - n_h])
+
+
+def device_planned(w, data, torch, engine, steps, warmup):
+    """The same step with the refresh plan made on the GPU between scoring and re-rotation
+    (cs_plan_refresh), captured in a HIP graph: nothing passes through the host inside the step.
+    Row lists are sized to capacities 1/8 above the step's row counts, rounded up to 256; the
+    consumers run over the capacities and skip the padding.  For comparison, the host route the
+    default step keeps outside its timed region: copy the offsets back, plan on the host, copy the
+    lists to the device."""
+    import numpy as np
+    from paper_2604_06036_amd import planner
+    cap = lambda n: (n + n // 8 + 255) // 256 * 256
+    info = data.info
+    step = engine.DevicePlannedStep(data, reuse_cap=cap(info["n_reuse"]), q_cap=cap(info["n_q"]))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    totals = step.totals.cpu().tolist()
+    if totals != [info["n_reuse"], info["n_q"], 0, 0]:
+        raise RuntimeError(f"device plan totals {totals} differ from the host plan's")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step.run()
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_step = 1e3 * (time.perf_counter() - t0) / steps
+    t_plan = event_time(torch, step.plan_refresh, max(3, min(steps, 20)))
+
+    def host_route():
+        off = step.kept_off.cpu().numpy()                                   # waits for the scoring call
+        counts = np.diff(off).reshape(w.n_streams, w.stride).astype(np.int32)
+        types = data.frame_type.reshape(w.n_streams, w.stride)
+        pl = planner.plan_slide(data.old_layout, types, counts, data.plan.layout.block_table, w.tokens_per_frame)
+        for a in (pl.src_slot, pl.dst_slot, pl.delta, pl.q_pos, pl.q_slot, pl.cu_q, pl.kv_len):
+            torch.from_numpy(a).to("cuda")
+        torch.cuda.synchronize()
+    host_route()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        host_route()
+    ms_host = 1e3 * (time.perf_counter() - t0) / 5
+    return dict(ms_per_step=ms_step, tokens_per_s=info["n_q"] / (ms_step * 1e-3), plan_call_ms=t_plan,
+                reuse_cap=step.reuse_cap, q_cap=step.q_cap, host_route_ms=ms_host)
 
 
 def cpu_baseline(w, data, step, torch):
@@ -331,6 +384,8 @@ def main():
     if not args.no_scaled_scoring:
         out["score_compact_scaled"] = scaled_scoring(w, torch, binding)
         out["kv_rerotate_axes"] = axes_rerotation(w, step, torch, binding, work["b_bytes"], reps)
+    if not args.no_device_plan:
+        out["device_planned_step"] = device_planned(w, data, torch, engine, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, data, step, torch)
     print(json.dumps(out))

@@ -273,6 +273,7 @@ class DevicePlannedStep(DeviceStep):
             self.ws_d = torch.zeros((max(8, self.ws_d_bytes),), dtype=torch.uint8, device=dev)
         self.n_rows_true, self.n_q_true = n_reuse, n_q
         self.n_q = self.q_cap
+        self.acc_in = self.acc.clone()
 
     def plan_refresh(self):
         w = self.data.workload
@@ -288,6 +289,9 @@ class DevicePlannedStep(DeviceStep):
             super().rerotate(in_place)
 
     def run(self):
+        # scoring updates the accumulated mask in place; a repeated run (graph replay) starts from
+        # the same mask so that every repetition plans the same step
+        self.acc.copy_(self.acc_in)
         self.score_compact()
         self.plan_refresh()
         self.rerotate()
