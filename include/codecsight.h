@@ -67,6 +67,47 @@ const char* cs_version(void);
 int cs_last_hip_error(void);
 
 /* ------------------------------------------------------------------------------------------
+ * (m) Block-to-patch projection.     Paper Sec. 3.3.1 ("Mapping codec changes to ViT patches":
+ *     every coding block's footprint in the source frame is projected onto the patch grid of the
+ *     preprocessed model input with the frame-to-input scaling, and a patch receives the largest
+ *     motion-vector magnitude, Eq. 1, among the blocks whose projected footprints overlap it);
+ *     Sec. 3.3.2 (patches overlapping intra-coded regions are retained).  Produces the `mv` and
+ *     `intra` inputs of cs_score_compact from a decoder's per-block output.
+ *
+ * Block m covers source pixels [x, x+w) x [y, y+h), clipped to the src_w x src_h frame; its image
+ * is [x sx, (x+w) sx) x [y sy, (y+h) sy) with sx = in_w/src_w, sy = in_h/src_h (a plain resize).
+ * Patch (r, c) of the grid_h x grid_w grid is [c patch, (c+1) patch) x [r patch, (r+1) patch) in
+ * input pixels; "overlap" is an intersection of positive area, decided in exact integer
+ * arithmetic.  Per frame f and patch i = r*grid_w + c:
+ *     mv[f][i]    = (dx, dy) of the overlapping inter block with the largest dx^2 + dy^2, ties to
+ *                   the lexicographically largest (dx, dy) (so block order never matters);
+ *                   (0, 0) when no inter block overlaps
+ *     intra[f][i] = 1 if a block with CS_BLOCK_INTRA overlaps, else 0 (such blocks carry no vector
+ *                   and take no part in the maximum)
+ *
+ *  blocks      in   cs_block [cu_blocks[n_frames]], 16-byte aligned; frame f owns records
+ *                   cu_blocks[f] .. cu_blocks[f+1]-1, in any order
+ *  cu_blocks   in   int32 [n_frames+1], non-decreasing
+ *  mv          out  int16 [n_frames][grid_h*grid_w][2], 4-byte aligned;  intra  out  uint8 [n_frames][grid_h*grid_w]
+ * All pointers are device memory.  Bit exact (integer work).
+ * Errors: CS_EINVAL (null pointer, negative n_frames, a size < 1), CS_EUNSUPPORTED (a frame or
+ *         input dimension > 16384, patch > 1024, grid_h*grid_w > 7168, misaligned blocks / mv),
+ *         CS_EHIP.  n_frames == 0 returns CS_OK.
+ * ------------------------------------------------------------------------------------------ */
+#define CS_BLOCK_INTRA 1u      /* cs_block.flags bit 0: intra-coded, dx/dy meaningless */
+
+typedef struct cs_block {
+  uint16_t x, y;               /* top-left corner, source-frame pixels */
+  uint16_t w, h;               /* size, source-frame pixels            */
+  int16_t dx, dy;              /* motion vector (any fixed unit, e.g. quarter pel) */
+  uint32_t flags;
+} cs_block;
+
+int cs_project_blocks(const cs_block* blocks, const int32_t* cu_blocks, int32_t n_frames,
+                      int32_t src_w, int32_t src_h, int32_t in_w, int32_t in_h, int32_t patch,
+                      int32_t grid_h, int32_t grid_w, int16_t* mv, uint8_t* intra, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * (a) Change scoring + ordered token compaction.       Paper Sec. 3.3.1-3.3.2, Eq. 1, 3, 4, 5,
  *     "Temporal stabilization within a GOP", "Adapting sparsity to the model layout".
  *

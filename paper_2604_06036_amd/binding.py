@@ -26,7 +26,7 @@ CS_KV_BLOCK = 16
 _ERR = {CS_EINVAL: "CS_EINVAL", CS_EUNSUPPORTED: "CS_EUNSUPPORTED", CS_EHIP: "CS_EHIP",
         CS_EWORKSPACE: "CS_EWORKSPACE"}
 
-EXPORTS = ("cs_version", "cs_last_hip_error", "cs_score_compact_workspace", "cs_score_compact",
+EXPORTS = ("cs_version", "cs_last_hip_error", "cs_project_blocks", "cs_score_compact_workspace", "cs_score_compact",
            "cs_plan_refresh_workspace", "cs_plan_refresh", "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
            "cs_window_prefill_attn_workspace",
            "cs_window_prefill_attn")
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
     L.cs_score_compact.restype = c.c_int
     L.cs_score_compact.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, u32, u32, i32,
                                    vp, vp, vp, vp, sz, vp]
+    L.cs_project_blocks.restype = c.c_int
+    L.cs_project_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     L.cs_plan_refresh_workspace.restype = sz
     L.cs_plan_refresh_workspace.argtypes = [i32, i32]
     L.cs_plan_refresh.restype = c.c_int
@@ -151,6 +153,20 @@ def cs_kv_rerotate(k_cache, v_cache, src_slot, dst_slot, delta, n_rows, n_layers
         _ptr(k_cache), _ptr(v_cache), _ptr(src_slot), _ptr(dst_slot), _ptr(delta), n_rows, n_layers,
         n_kv_heads, head_dim, stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype,
         _stream()))
+
+
+def cs_project_blocks(blocks, cu_blocks, n_frames, src_w, src_h, in_w, in_h, patch, grid_h, grid_w, mv, intra,
+                      n_blocks=None):
+    """blocks: uint8 / int32 tensor holding the 16-byte records; n_blocks (= cu_blocks[-1], known to the
+    caller) only serves the length check."""
+    fn = "cs_project_blocks"
+    _need(fn, cu_blocks, n_frames + 1, "cu_blocks")
+    if n_blocks is not None and blocks is not None and blocks.numel() * blocks.element_size() < 16 * n_blocks:
+        raise ValueError(f"{fn}: blocks holds fewer than {n_blocks} records")
+    if grid_h > 0 and grid_w > 0:
+        _need(fn, mv, n_frames * grid_h * grid_w * 2, "mv"); _need(fn, intra, n_frames * grid_h * grid_w, "intra")
+    _check(fn, lib().cs_project_blocks(_ptr(blocks), _ptr(cu_blocks), n_frames, src_w, src_h, in_w, in_h, patch,
+                                       grid_h, grid_w, _ptr(mv), _ptr(intra), _stream()))
 
 
 def cs_plan_refresh_workspace(n_streams, window) -> int:

@@ -204,6 +204,73 @@ def batch_metadata(w: Workload) -> BatchMeta:
     )
 
 
+# 16-byte coding-block record of the block-to-patch projection (layout of cs_block in the C header)
+BLOCK_DTYPE = np.dtype([("x", "<u2"), ("y", "<u2"), ("w", "<u2"), ("h", "<u2"),
+                        ("dx", "<i2"), ("dy", "<i2"), ("flags", "<u4")])
+MODEL_PATCH = 28             # input pixels per patch-grid cell (14-pixel ViT patches merged 2 x 2)
+SOURCE_SIZE = (1920, 1080)   # decoded stream resolution (coded in 16 x 16 macroblocks: 120 x 68)
+
+# macroblock partitions (offset x, offset y, width, height): one 16x16, two 16x8, two 8x16, four 8x8
+_PARTITIONS = (
+    ((0, 0, 16, 16),),
+    ((0, 0, 16, 8), (0, 8, 16, 8)),
+    ((0, 0, 8, 16), (8, 0, 8, 16)),
+    ((0, 0, 8, 8), (8, 0, 8, 8), (0, 8, 8, 8), (8, 8, 8, 8)),
+)
+# partition mix of a P-frame's macroblocks (last entry: intra-coded), in still and in moving regions
+_PARTITION_P_STILL = (0.70, 0.08, 0.08, 0.138, 0.002)
+_PARTITION_P_MOVING = (0.40, 0.12, 0.12, 0.31, 0.05)
+
+
+def input_size(w: Workload) -> Tuple[int, int]:
+    """(width, height) of the preprocessed model input whose patch grid the workload names."""
+    return w.grid_w * MODEL_PATCH, w.grid_h * MODEL_PATCH
+
+
+def block_frames(w: Workload, frame_type: np.ndarray, blob: np.ndarray, tag: int = 0):
+    """Per-block decoder output for a batch of frames, H.264-like: the source frame is tiled by
+    16 x 16 macroblocks (the last row sticks out of a 1080-line frame), each split into one, two or
+    four inter partitions with a vector of their own, or intra-coded (finer partitions and intra
+    macroblocks are more frequent where the scene moves); I-frames are all intra.
+    Vectors are drawn like the per-patch metadata: N(0, 24^2) where the block's centre falls on a
+    moving patch (`blob` [F, P] bool), N(0, 1) elsewhere, rounded to int16.
+    Returns (blocks [n] BLOCK_DTYPE, macroblock raster order, partitions in order; cu_blocks [F+1])."""
+    rng = _rng(w, 0xB10C5, tag)
+    src_w, src_h = SOURCE_SIZE
+    mb_w, mb_h = (src_w + 15) // 16, (src_h + 15) // 16
+    n_mb = mb_w * mb_h
+    mb_x = (np.arange(n_mb) % mb_w) * 16
+    mb_y = (np.arange(n_mb) // mb_w) * 16
+    out, cu = [], [0]
+    for f in range(int(frame_type.shape[0])):
+        mcx = np.minimum((mb_x + 8.0) * w.grid_w / src_w, w.grid_w - 1).astype(np.int64)
+        mcy = np.minimum((mb_y + 8.0) * w.grid_h / src_h, w.grid_h - 1).astype(np.int64)
+        kind = np.where(blob[f, mcy * w.grid_w + mcx], rng.choice(5, size=n_mb, p=_PARTITION_P_MOVING),
+                        rng.choice(5, size=n_mb, p=_PARTITION_P_STILL))
+        if frame_type[f] == FRAME_I:
+            kind = np.full(n_mb, 4)
+        parts, order = [], []
+        for k in range(5):
+            mbs = np.flatnonzero(kind == k)
+            for j, (ox, oy, pw, ph) in enumerate(_PARTITIONS[k] if k < 4 else _PARTITIONS[0]):
+                b = np.zeros(mbs.size, BLOCK_DTYPE)
+                b["x"], b["y"], b["w"], b["h"] = mb_x[mbs] + ox, mb_y[mbs] + oy, pw, ph
+                b["flags"] = 1 if k == 4 else 0
+                parts.append(b)
+                order.append(mbs * 4 + j)
+        b = np.concatenate(parts)[np.argsort(np.concatenate(order), kind="stable")]
+        # which patch the block's centre falls on (only to place the motion, no part of the method)
+        cx = np.minimum((b["x"] + b["w"] / 2.0) * w.grid_w / src_w, w.grid_w - 1).astype(np.int64)
+        cy = np.minimum((b["y"] + b["h"] / 2.0) * w.grid_h / src_h, w.grid_h - 1).astype(np.int64)
+        sigma = np.where(blob[f, cy * w.grid_w + cx], 24.0, 1.0)
+        vec = np.clip(np.rint(rng.normal(0.0, 1.0, size=(b.size, 2)) * sigma[:, None]), -32768, 32767)
+        inter = b["flags"] == 0
+        b["dx"][inter], b["dy"][inter] = vec[inter, 0], vec[inter, 1]
+        out.append(b)
+        cu.append(cu[-1] + b.size)
+    return np.concatenate(out) if out else np.zeros(0, BLOCK_DTYPE), np.asarray(cu, np.int32)
+
+
 def block_ids(w: Workload, n_blocks_needed: int, tag: int = 0) -> np.ndarray:
     """A pool of `n_blocks_needed` distinct physical block ids: shuffled, or 0..n-1 in order."""
     ids = np.arange(n_blocks_needed, dtype=np.int32)

@@ -66,6 +66,26 @@ def test_host_side_argument_errors(lib):
     assert L.cs_score_compact(z, z, z, one, one, z, 1, 1, 16, 16, 1, 0, 0, 0, one, one, one, one, 64, z) == binding.CS_EINVAL
     assert L.cs_score_compact(one, z, z, one, one, z, 1, 1, 16, 16, 1, 0, 0, 0, one, one, one, z, 0, z) == binding.CS_EWORKSPACE
     assert L.cs_score_compact(one, z, z, one, one, z, 8, 8, 16, 16, 1, 0, 0, 0, one, one, one, one, 8, z) == binding.CS_EWORKSPACE
+    # (m) block-to-patch projection
+    def proj(**kw):
+        a = dict(b=one, cu=one, nf=2, sw=1920, sh=1080, iw=448, ih=448, p=28, gh=16, gw=16, mv=one, it=one)
+        a.update(kw)
+        return L.cs_project_blocks(a["b"], a["cu"], a["nf"], a["sw"], a["sh"], a["iw"], a["ih"], a["p"], a["gh"],
+                                   a["gw"], a["mv"], a["it"], z)
+    assert proj(nf=-1) == binding.CS_EINVAL
+    assert proj(sw=0) == binding.CS_EINVAL
+    assert proj(p=0) == binding.CS_EINVAL
+    assert proj(gw=0) == binding.CS_EINVAL
+    assert proj(b=z) == binding.CS_EINVAL
+    assert proj(mv=z) == binding.CS_EINVAL
+    assert proj(it=z) == binding.CS_EINVAL
+    assert proj(nf=0, b=z, cu=z, mv=z, it=z) == binding.CS_OK
+    assert proj(sw=16385) == binding.CS_EUNSUPPORTED
+    assert proj(ih=20000) == binding.CS_EUNSUPPORTED
+    assert proj(p=1025) == binding.CS_EUNSUPPORTED
+    assert proj(gh=128, gw=57) == binding.CS_EUNSUPPORTED
+    assert proj(b=ctypes.c_void_p(24)) == binding.CS_EUNSUPPORTED
+    assert proj(mv=ctypes.c_void_p(18)) == binding.CS_EUNSUPPORTED
     # (p) the device planner
     def plan(**kw):
         a = dict(ot=one, oc=one, nt=one, ko=one, bto=one, mbo=4, btn=one, mbn=4, ns=2, w=8, s=1, nt_=16, t=64,

@@ -146,6 +146,112 @@ def test_score_compact_i_frame_ignores_metadata(cs):
     assert a[0][0].all() and a[0][2].all()
 
 
+# =============================================================================== (m) projection
+def _project_gpu(cs, blocks, cu, geom):
+    n_frames = len(cu) - 1
+    gh, gw = geom[5], geom[6]
+    raw = torch.from_numpy(np.ascontiguousarray(blocks).view(np.uint8).copy()) if blocks.size else torch.zeros(16, dtype=torch.uint8)
+    d_blocks = raw.to(DEV)
+    d_cu = torch.from_numpy(np.asarray(cu, np.int32)).to(DEV)
+    mv = torch.full((max(1, n_frames), gh * gw, 2), -99, dtype=torch.int16, device=DEV)
+    intra = torch.full((max(1, n_frames), gh * gw), 77, dtype=torch.uint8, device=DEV)
+    cs.cs_project_blocks(d_blocks, d_cu, n_frames, geom[0], geom[1], geom[2], geom[3], geom[4], gh, gw, mv, intra,
+                         n_blocks=int(blocks.size))
+    torch.cuda.synchronize()
+    return mv.cpu().numpy()[:n_frames], intra.cpu().numpy()[:n_frames]
+
+
+def _random_block_frames(rng, counts, src_w, src_h, max_size, spread, p_intra=0.1, extremes=False):
+    from oracle import projection_oracle as po
+    n = int(sum(counts))
+    b = np.zeros(n, po.BLOCK_DTYPE)
+    b["x"] = rng.integers(0, src_w + 3, size=n)                 # some start outside the frame
+    b["y"] = rng.integers(0, src_h + 3, size=n)
+    b["w"] = rng.integers(0, max_size + 1, size=n)              # some have no area
+    b["h"] = rng.integers(0, max_size + 1, size=n)
+    b["dx"] = rng.integers(-spread, spread + 1, size=n)
+    b["dy"] = rng.integers(-spread, spread + 1, size=n)
+    b["flags"] = (rng.random(n) < p_intra).astype(np.uint32) | (rng.integers(0, 4, size=n).astype(np.uint32) << 1)
+    if extremes and n >= 4:
+        b["dx"][:4], b["dy"][:4] = (-32768, 32767, -32768, 0), (-32768, 32767, 32767, -32768)
+        b["flags"][:4] = 0
+        b["w"][:4], b["h"][:4] = max(1, max_size), max(1, max_size)
+    cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    return b, cu
+
+
+PROJECT_CASES = [
+    # src_w, src_h, in_w, in_h, patch, gh, gw | blocks per frame | max block | vector spread | extremes
+    ((64, 48, 32, 24, 8, 3, 4), [7, 0, 30], 20, 9, False),
+    ((30, 10, 20, 10, 5, 2, 4), [12, 12], 8, 3, False),
+    ((1920, 1080, 448, 448, 28, 16, 16), [3000, 1, 5000], 64, 40, True),
+    ((1920, 1088, 1288, 728, 28, 26, 46), [9000], 32, 30, False),
+    ((17, 23, 12, 18, 3, 6, 4), [40] * 5, 12, 2, False),                  # many ties
+    ((13, 9, 26, 27, 9, 3, 3), [25], 6, 5, False),                        # upscaling
+    ((31, 19, 14, 14, 7, 1, 1), [25], 31, 5, False),                      # grid smaller than the input
+    ((16384, 16384, 16384, 16384, 1024, 16, 16), [500], 5000, 32767, True),   # the largest numerators
+    ((4000, 3000, 7168, 14, 14, 1, 512), [2000], 300, 100, False),
+    ((640, 360, 1792, 56, 14, 4, 128), [4000, 4000], 40, 100, True),
+    ((1, 1, 1, 1, 1, 1, 1), [3], 1, 3, False),
+]
+
+
+@pytest.mark.parametrize("case", range(len(PROJECT_CASES)))
+def test_project_blocks(cs, case):
+    """Projected vectors and intra flags equal the oracle's bit for bit (the tie rule makes the
+    result unique), on awkward scalings, clipped and empty footprints and extreme vectors."""
+    from oracle import projection_oracle as po
+    geom, counts, max_size, spread, extremes = PROJECT_CASES[case]
+    say(f"project_blocks case {case}: geometry {geom} blocks {counts}")
+    rng = np.random.default_rng(8000 + case)
+    blocks, cu = _random_block_frames(rng, counts, geom[0], geom[1], max_size, spread, extremes=extremes)
+    mv_w, intra_w = po.project_blocks(blocks, cu, *geom)
+    mv_g, intra_g = _project_gpu(cs, blocks, cu, geom)
+    assert np.array_equal(mv_g, mv_w) and np.array_equal(intra_g, intra_w)
+    # block order inside a frame does not matter
+    perm = np.concatenate([cu[f] + rng.permutation(cu[f + 1] - cu[f]) for f in range(len(cu) - 1)]).astype(np.int64)
+    mv_p, intra_p = _project_gpu(cs, blocks[perm], cu, geom)
+    assert np.array_equal(mv_p, mv_w) and np.array_equal(intra_p, intra_w)
+
+
+def test_project_blocks_no_frames(cs):
+    say("project_blocks with no frames")
+    from oracle import projection_oracle as po
+    mv, intra = _project_gpu(cs, np.zeros(0, po.BLOCK_DTYPE), np.zeros(1, np.int32), (64, 48, 32, 24, 8, 3, 4))
+    assert mv.shape[0] == 0 and intra.shape[0] == 0
+
+
+@pytest.mark.parametrize("w", [synth.small_variant(synth.CFG2, n_streams=3), synth.CFG3P], ids=lambda w: w.name)
+def test_projection_feeds_scoring(cs, w):
+    """Decoder-shaped block lists (macroblock partitions of a 1920x1080 frame) -> projection ->
+    scoring, HIP chain against oracle chain: the projected metadata and the kept-token lists agree."""
+    from oracle import projection_oracle as po
+    say(f"projection -> scoring: {w.name}")
+    src_w, src_h = synth.SOURCE_SIZE
+    in_w, in_h = synth.input_size(w)
+    geom = (src_w, src_h, in_w, in_h, synth.MODEL_PATCH, w.grid_h, w.grid_w)
+    ftypes, blobs = [], []
+    for s in range(w.n_streams):
+        m = synth.stream_metadata(w, s)
+        ftypes.append(m.frame_type[-w.stride:])
+        blobs.append(m.blob[-w.stride:])
+    ftype = np.concatenate(ftypes)
+    blocks, cu = synth.block_frames(w, ftype, np.concatenate(blobs))
+    say(f"  {blocks.size} blocks in {ftype.size} frames")
+    mv_w, intra_w = po.project_blocks(blocks.view(po.BLOCK_DTYPE), cu, *geom)
+    mv_g, intra_g = _project_gpu(cs, blocks, cu, geom)
+    assert np.array_equal(mv_g, mv_w) and np.array_equal(intra_g, intra_w)
+    cu_frames = (np.arange(w.n_streams + 1) * w.stride).astype(np.int32)
+    acc = np.zeros((w.n_streams, w.patches), np.uint8)
+    want = oc.score_compact(mv_w, None, intra_w, ftype, cu_frames, acc.copy(), w.grid_h, w.grid_w, w.group,
+                            w.tau_mv_sq, 0, False)
+    got = _score_gpu(cs, mv_g, None, intra_g, ftype, cu_frames, acc.copy(), w.grid_h, w.grid_w, w.group,
+                     w.tau_mv_sq, 0, False)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[2], want[2])
+    assert np.array_equal(got[1][: want[1].size], want[1])
+    say(f"  kept {want[1].size} of {ftype.size * w.tokens_per_frame} tokens")
+
+
 # =============================================================================== (b) re-rotation
 def _pool(rng, shape, dtype):
     x = torch.from_numpy(rng.normal(size=shape).astype(np.float32))
