@@ -127,6 +127,44 @@ def scaled_scoring(w, torch, binding):
                 bytes=nbytes, GBps=nbytes / ms / 1e6, frac_of_hbm_peak=nbytes / ms / 1e6 / PEAK_HBM_GBS)
 
 
+def block_projection(w, torch, binding, reps):
+    """cs_project_blocks: decoder-shaped block lists (macroblock partitions of a 1920 x 1080 frame)
+    to the workload's patch grid.  Real shape = the step's own new frames; scaled = the same frames
+    repeated until the block records exceed 256 MB (bandwidth rather than launch latency)."""
+    import numpy as np
+    from paper_2604_06036_amd import synth
+    src_w, src_h = synth.SOURCE_SIZE
+    in_w, in_h = synth.input_size(w)
+    ftypes, blobs = [], []
+    for s in range(min(w.n_streams, 64)):
+        m = synth.stream_metadata(w, s)
+        ftypes.append(m.frame_type[-w.stride:])
+        blobs.append(m.blob[-w.stride:])
+    blocks, cu = synth.block_frames(w, np.concatenate(ftypes), np.concatenate(blobs))
+    out = {}
+    for label in ("real shape", "scaled batch"):
+        n_frames, n_blocks = int(cu.shape[0]) - 1, int(blocks.shape[0])
+        d_blocks = torch.from_numpy(blocks.view(np.uint8).copy()).cuda()
+        d_cu = torch.from_numpy(cu).cuda()
+        mv = torch.empty((n_frames, w.patches, 2), dtype=torch.int16, device="cuda")
+        intra = torch.empty((n_frames, w.patches), dtype=torch.uint8, device="cuda")
+        call = lambda: binding.cs_project_blocks(d_blocks, d_cu, n_frames, src_w, src_h, in_w, in_h,
+                                                 synth.MODEL_PATCH, w.grid_h, w.grid_w, mv, intra, n_blocks=n_blocks)
+        for _ in range(2):
+            call()
+        ms = event_time(torch, call, reps)
+        nbytes = n_blocks * 16 + n_frames * (w.patches * 5 + 4)
+        out[label] = dict(frames=n_frames, blocks=n_blocks, ms=ms, bytes=nbytes, GBps=nbytes / ms / 1e6,
+                          frac_of_hbm_peak=nbytes / ms / 1e6 / PEAK_HBM_GBS)
+        if label == "real shape":
+            rep = max(1, (288 << 20) // max(1, n_blocks * 16))
+            off = (np.arange(rep, dtype=np.int64)[:, None] * n_blocks + cu[None, :-1]).reshape(-1)
+            cu = np.concatenate([off, [rep * n_blocks]]).astype(np.int32)
+            blocks = np.tile(blocks, rep)
+        del d_blocks, mv, intra
+    return out
+
+
 def axes_rerotation(w, step, torch, binding, b_bytes, reps):
     """cs_kv_rerotate_axes (three-axis RoPE correction) on the step's own reuse plan: the window
     slides in time only, so the shift is (delta, 0, 0); frequency pairs are mapped to (t, h, w) in
@@ -383,6 +421,7 @@ def main():
         out["copy_calibration"] = copy_calibration(torch)
     if not args.no_scaled_scoring:
         out["score_compact_scaled"] = scaled_scoring(w, torch, binding)
+        out["block_projection"] = block_projection(w, torch, binding, reps)
         out["kv_rerotate_axes"] = axes_rerotation(w, step, torch, binding, work["b_bytes"], reps)
     if not args.no_device_plan:
         out["device_planned_step"] = device_planned(w, data, torch, engine, args.steps, args.warmup)

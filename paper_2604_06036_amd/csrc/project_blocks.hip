@@ -17,7 +17,8 @@
 
 namespace {
 
-constexpr int kProjectThreads = 512;
+constexpr int kProjectThreads = 1024;
+constexpr int kBatch = 4;
 constexpr int kNumeratorBits = 29;
 
 struct ExactDiv {                // q = (n * mul) >> shift == n / d for every n < 2^kNumeratorBits
@@ -60,17 +61,16 @@ __global__ __launch_bounds__(kProjectThreads) void project_blocks_kernel(Project
   __syncthreads();
 
   const int begin = p.cu_blocks[frame], end = p.cu_blocks[frame + 1];
-  for (int i = begin + tid; i < end; i += kProjectThreads) {
-    const cs::u32x4 rec = __builtin_nontemporal_load(p.blocks + i);
+  auto apply = [&](const cs::u32x4 rec) {
     const uint32_t x = rec.x & 0xffffu, y = rec.x >> 16, w = rec.y & 0xffffu, h = rec.y >> 16;
     const int dx = static_cast<int16_t>(rec.z & 0xffffu), dy = static_cast<int16_t>(rec.z >> 16);
     const bool is_intra = (rec.w & 1u) != 0;
     const uint32_t mag = static_cast<uint32_t>(dx * dx) + static_cast<uint32_t>(dy * dy);   // up to 2^31
-    if (!is_intra && mag == 0u) continue;                     // a zero vector changes no patch
+    if (!is_intra && mag == 0u) return;                       // a zero vector changes no patch
     // footprint clipped to the frame; nothing left -> no footprint
     const uint32_t lo_x = min(x, p.src_w), hi_x = min(x + w, p.src_w);
     const uint32_t lo_y = min(y, p.src_h), hi_y = min(y + h, p.src_h);
-    if (hi_x <= lo_x || hi_y <= lo_y) continue;
+    if (hi_x <= lo_x || hi_y <= lo_y) return;
     // patch columns c with lo*in < (c+1)*den and hi*in > c*den (positive overlap), same for rows
     const int c0 = static_cast<int>(div_by(lo_x * p.in_w, p.div_x));
     const int c1 = min(static_cast<int>(div_by(hi_x * p.in_w + p.den_x - 1u, p.div_x)) - 1, p.grid_w - 1);
@@ -88,6 +88,17 @@ __global__ __launch_bounds__(kProjectThreads) void project_blocks_kernel(Project
           atomicMax(&s_key[cell], key);
         }
       }
+  };
+  // kBatch records in flight per thread (a record past the end is replaced by an empty one)
+  for (int i0 = begin + tid; i0 < end; i0 += kProjectThreads * kBatch) {
+    cs::u32x4 rec[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = i0 + u * kProjectThreads;
+      rec[u] = i < end ? __builtin_nontemporal_load(p.blocks + i) : cs::u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) apply(rec[u]);
   }
   __syncthreads();
 
