@@ -108,6 +108,38 @@ int cs_project_blocks(const cs_block* blocks, const int32_t* cu_blocks, int32_t 
                       int32_t grid_h, int32_t grid_w, int16_t* mv, uint8_t* intra, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * (r) Residual proxy.     Paper Sec. 4, "Codec Processing" (the decoder exposes no prediction
+ *     residuals; each patch's residual score is the mean absolute difference from the
+ *     motion-compensated prediction of the previous decoded frame); it stands in for the block
+ *     residual of Eq. 2 and feeds the rescue rule of Eq. 4.  Produces the `sad` input of
+ *     cs_score_compact.
+ *
+ * Frames are 8-bit luma planes at source resolution.  The motion field holds one quarter-pixel
+ * vector (dx, dy) per cell x cell pixel cell (intra cells: (0, 0)).  For pixel (x, y) of frame f:
+ *     (ox, oy)   = (floor((dx + 2) / 4), floor((dy + 2) / 4))        whole-pixel vector
+ *     pred(x, y) = prev[f][clamp(y + oy, 0, src_h-1)][clamp(x + ox, 0, src_w-1)]
+ * The pixel belongs to patch column floor(x * in_w / (patch * src_w)) and row
+ * floor(y * in_h / (patch * src_h)) (the plain resize of cs_project_blocks); pixels outside the
+ * grid_h x grid_w grid are ignored.  Per patch i with n_i pixels:
+ *     res[f][i] = floor(256 * sum |cur - pred| / n_i)      (1/256 grey levels; 0 when n_i = 0)
+ *
+ *  cur, prev   in   uint8, frame f at + f*frame_stride, row y at + y*pitch (bytes); 16-byte aligned
+ *  mv_field    in   int16 [n_frames][ceil(src_h/cell)][ceil(src_w/cell)][2], 4-byte aligned
+ *  res         out  uint32 [n_frames][grid_h*grid_w], 4-byte aligned (also the accumulator: the
+ *                   call clears it first)
+ * All pointers are device memory.  Bit exact (integer work).
+ * Errors: CS_EINVAL (null pointer, negative n_frames, a size < 1, pitch < src_w, frame_stride <
+ *         pitch*src_h), CS_EUNSUPPORTED (cell not 4, 8 or 16; a frame or input dimension > 16384;
+ *         patch > 1024; grid_w > 8192; pitch or frame_stride not a multiple of 16, pitch below
+ *         src_w rounded up to 16; misaligned pointers; patch columns narrower than 4 source
+ *         pixels, i.e. patch*src_w < 4*in_w), CS_EHIP.  n_frames == 0 returns CS_OK.
+ * ------------------------------------------------------------------------------------------ */
+int cs_residual_proxy(const uint8_t* cur, const uint8_t* prev, const int16_t* mv_field,
+                      int32_t n_frames, int32_t src_w, int32_t src_h, int64_t pitch,
+                      int64_t frame_stride, int32_t cell, int32_t in_w, int32_t in_h, int32_t patch,
+                      int32_t grid_h, int32_t grid_w, uint32_t* res, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * (a) Change scoring + ordered token compaction.       Paper Sec. 3.3.1-3.3.2, Eq. 1, 3, 4, 5,
  *     "Temporal stabilization within a GOP", "Adapting sparsity to the model layout".
  *

@@ -26,7 +26,7 @@ CS_KV_BLOCK = 16
 _ERR = {CS_EINVAL: "CS_EINVAL", CS_EUNSUPPORTED: "CS_EUNSUPPORTED", CS_EHIP: "CS_EHIP",
         CS_EWORKSPACE: "CS_EWORKSPACE"}
 
-EXPORTS = ("cs_version", "cs_last_hip_error", "cs_project_blocks", "cs_score_compact_workspace", "cs_score_compact",
+EXPORTS = ("cs_version", "cs_last_hip_error", "cs_project_blocks", "cs_residual_proxy", "cs_score_compact_workspace", "cs_score_compact",
            "cs_plan_refresh_workspace", "cs_plan_refresh", "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
            "cs_window_prefill_attn_workspace",
            "cs_window_prefill_attn")
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
                                    vp, vp, vp, vp, sz, vp]
     L.cs_project_blocks.restype = c.c_int
     L.cs_project_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    L.cs_residual_proxy.restype = c.c_int
+    L.cs_residual_proxy.argtypes = [vp, vp, vp, i32, i32, i32, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp]
     L.cs_plan_refresh_workspace.restype = sz
     L.cs_plan_refresh_workspace.argtypes = [i32, i32]
     L.cs_plan_refresh.restype = c.c_int
@@ -167,6 +169,17 @@ def cs_project_blocks(blocks, cu_blocks, n_frames, src_w, src_h, in_w, in_h, pat
         _need(fn, mv, n_frames * grid_h * grid_w * 2, "mv"); _need(fn, intra, n_frames * grid_h * grid_w, "intra")
     _check(fn, lib().cs_project_blocks(_ptr(blocks), _ptr(cu_blocks), n_frames, src_w, src_h, in_w, in_h, patch,
                                        grid_h, grid_w, _ptr(mv), _ptr(intra), _stream()))
+
+
+def cs_residual_proxy(cur, prev, mv_field, n_frames, src_w, src_h, pitch, frame_stride, cell, in_w, in_h, patch,
+                      grid_h, grid_w, res):
+    fn = "cs_residual_proxy"
+    if n_frames > 0 and cell > 0:
+        _need(fn, cur, n_frames * frame_stride, "cur"); _need(fn, prev, n_frames * frame_stride, "prev")
+        _need(fn, mv_field, n_frames * (-(-src_h // cell)) * (-(-src_w // cell)) * 2, "mv_field")
+        _need(fn, res, n_frames * grid_h * grid_w, "res")
+    _check(fn, lib().cs_residual_proxy(_ptr(cur), _ptr(prev), _ptr(mv_field), n_frames, src_w, src_h, pitch,
+                                       frame_stride, cell, in_w, in_h, patch, grid_h, grid_w, _ptr(res), _stream()))
 
 
 def cs_plan_refresh_workspace(n_streams, window) -> int:

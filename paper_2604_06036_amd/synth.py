@@ -271,6 +271,52 @@ def block_frames(w: Workload, frame_type: np.ndarray, blob: np.ndarray, tag: int
     return np.concatenate(out) if out else np.zeros(0, BLOCK_DTYPE), np.asarray(cu, np.int32)
 
 
+def motion_field(blocks: np.ndarray, cu_blocks: np.ndarray, cell: int = 4) -> np.ndarray:
+    """The block lists of `block_frames` rasterised to a regular field of cell x cell pixel cells:
+    int16 [F, ceil(H/cell), ceil(W/cell), 2]; intra blocks leave (0, 0).  Pure re-formatting."""
+    src_w, src_h = SOURCE_SIZE
+    n_frames = int(cu_blocks.shape[0]) - 1
+    field = np.zeros((n_frames, -(-src_h // cell), -(-src_w // cell), 2), np.int16)
+    for f in range(n_frames):
+        b = blocks[cu_blocks[f]:cu_blocks[f + 1]]
+        b = b[b["flags"] == 0]
+        for size in np.unique(np.stack([b["w"], b["h"]], axis=1), axis=0):
+            sel = b[(b["w"] == size[0]) & (b["h"] == size[1])]
+            for oy in range(0, int(size[1]), cell):
+                for ox in range(0, int(size[0]), cell):
+                    cy, cx = (sel["y"] + oy) // cell, (sel["x"] + ox) // cell
+                    ok = (cy < field.shape[1]) & (cx < field.shape[2])
+                    field[f, cy[ok], cx[ok], 0] = sel["dx"][ok]
+                    field[f, cy[ok], cx[ok], 1] = sel["dy"][ok]
+    return field
+
+
+def decoded_frames(w: Workload, n_frames: int, blob: np.ndarray, tag: int = 0):
+    """(cur, prev) uint8 [F, 1080, 1920] luma planes: prev is a smooth random texture; cur repeats
+    it with sensor noise (sigma 1.5 grey levels), shows it displaced by (3, -2) pixels where the
+    scene moves (`blob` [F, P] bool on the patch grid) and 30 grey levels brighter on a few discs
+    that do not move (appearance change without motion: what residual rescue is for)."""
+    rng = _rng(w, 0xF4A3E, tag)
+    src_w, src_h = SOURCE_SIZE
+    cur = np.empty((n_frames, src_h, src_w), np.uint8)
+    prev = np.empty_like(cur)
+    yy, xx = np.meshgrid(np.arange(src_h), np.arange(src_w), indexing="ij")
+    py = np.minimum(yy * w.grid_h // src_h, w.grid_h - 1)
+    px = np.minimum(xx * w.grid_w // src_w, w.grid_w - 1)
+    for f in range(n_frames):
+        coarse = rng.integers(40, 200, size=(src_h // 8 + 1, src_w // 8 + 1)).astype(np.float32)
+        tex = np.kron(coarse, np.ones((8, 8), np.float32))[:src_h, :src_w] + rng.normal(0.0, 6.0, size=(src_h, src_w))
+        p = np.clip(np.rint(tex), 0, 255)
+        moving = blob[f].reshape(w.grid_h, w.grid_w)[py, px]
+        c = np.where(moving, np.roll(p, shift=(-2, 3), axis=(0, 1)), p) + rng.normal(0.0, 1.5, size=p.shape)
+        for _ in range(3):
+            cy, cx, rad = rng.uniform(0, src_h), rng.uniform(0, src_w), rng.uniform(40, 120)
+            c = c + 30.0 * ((yy - cy) ** 2 + (xx - cx) ** 2 <= rad * rad)
+        prev[f] = p.astype(np.uint8)
+        cur[f] = np.clip(np.rint(c), 0, 255).astype(np.uint8)
+    return cur, prev
+
+
 def block_ids(w: Workload, n_blocks_needed: int, tag: int = 0) -> np.ndarray:
     """A pool of `n_blocks_needed` distinct physical block ids: shuffled, or 0..n-1 in order."""
     ids = np.arange(n_blocks_needed, dtype=np.int32)

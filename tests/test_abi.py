@@ -86,6 +86,30 @@ def test_host_side_argument_errors(lib):
     assert proj(gh=128, gw=57) == binding.CS_EUNSUPPORTED
     assert proj(b=ctypes.c_void_p(24)) == binding.CS_EUNSUPPORTED
     assert proj(mv=ctypes.c_void_p(18)) == binding.CS_EUNSUPPORTED
+    # (r) residual proxy
+    def resid(**kw):
+        a = dict(cur=one, prev=one, f=one, nf=2, sw=1920, sh=1080, pitch=1920, fs=1920 * 1080, cell=4, iw=448,
+                 ih=448, p=28, gh=16, gw=16, res=one)
+        a.update(kw)
+        return L.cs_residual_proxy(a["cur"], a["prev"], a["f"], a["nf"], a["sw"], a["sh"], a["pitch"], a["fs"],
+                                   a["cell"], a["iw"], a["ih"], a["p"], a["gh"], a["gw"], a["res"], z)
+    assert resid(nf=-1) == binding.CS_EINVAL
+    assert resid(sh=0) == binding.CS_EINVAL
+    assert resid(pitch=1900) == binding.CS_EINVAL
+    assert resid(fs=1920 * 1000) == binding.CS_EINVAL
+    assert resid(cur=z) == binding.CS_EINVAL
+    assert resid(f=z) == binding.CS_EINVAL
+    assert resid(res=z) == binding.CS_EINVAL
+    assert resid(nf=0, cur=z, prev=z, f=z, res=z) == binding.CS_OK
+    assert resid(cell=5) == binding.CS_EUNSUPPORTED
+    assert resid(cell=32) == binding.CS_EUNSUPPORTED
+    assert resid(sw=1912, pitch=1912, fs=1912 * 1080) == binding.CS_EUNSUPPORTED      # pitch not a multiple of 16
+    assert resid(sw=1910, pitch=1910 + 2, fs=1912 * 1080) == binding.CS_EUNSUPPORTED
+    assert resid(fs=1920 * 1080 + 8) == binding.CS_EUNSUPPORTED
+    assert resid(prev=ctypes.c_void_p(24)) == binding.CS_EUNSUPPORTED
+    assert resid(res=ctypes.c_void_p(18)) == binding.CS_EUNSUPPORTED
+    assert resid(sw=64, sh=64, pitch=64, fs=4096, iw=456) == binding.CS_EUNSUPPORTED  # 28*64 < 4*456
+    assert resid(sw=20000, pitch=20000, fs=20000 * 1080) == binding.CS_EUNSUPPORTED
     # (p) the device planner
     def plan(**kw):
         a = dict(ot=one, oc=one, nt=one, ko=one, bto=one, mbo=4, btn=one, mbn=4, ns=2, w=8, s=1, nt_=16, t=64,

@@ -252,6 +252,107 @@ def test_projection_feeds_scoring(cs, w):
     say(f"  kept {want[1].size} of {ftype.size * w.tokens_per_frame} tokens")
 
 
+# =============================================================================== (r) residual proxy
+def _residual_gpu(cs, cur, prev, field, cell, in_w, in_h, patch, gh, gw, pad=0):
+    """cur, prev: uint8 [F, H, W] on the host; rows are copied into planes with pitch = W rounded
+    up to 16 (+ pad) whose padding bytes hold garbage, so a read past a row's end would show."""
+    n_frames, h, w = cur.shape
+    pitch = -(-w // 16) * 16 + pad
+    def plane(a, fill):
+        t = np.full((max(1, n_frames), h, pitch), fill, np.uint8)
+        t[:n_frames, :, :w] = a
+        return torch.from_numpy(t).to(DEV)
+    d_cur, d_prev = plane(cur, 201), plane(prev, 57)
+    d_field = torch.from_numpy(np.ascontiguousarray(field)).to(DEV) if field.size else torch.zeros(2, dtype=torch.int16, device=DEV)
+    res = torch.full((max(1, n_frames), gh * gw), 12345, dtype=torch.int32, device=DEV)
+    cs.cs_residual_proxy(d_cur, d_prev, d_field, n_frames, w, h, pitch, h * pitch, cell, in_w, in_h, patch, gh, gw, res)
+    torch.cuda.synchronize()
+    return res.cpu().numpy().view(np.uint32)[:n_frames]
+
+
+RESIDUAL_CASES = [
+    # frames, h, w, cell, in_w, in_h, patch, gh, gw, vector spread (quarter pixels), pad
+    (1, 4, 8, 4, 4, 2, 2, 1, 2, 8, 0),
+    (2, 12, 20, 4, 15, 9, 3, 3, 5, 40, 0),
+    (3, 10, 30, 4, 20, 10, 5, 2, 4, 60, 16),
+    (1, 37, 53, 8, 26, 27, 9, 3, 2, 200, 0),            # width and height not multiples of the cell
+    (2, 64, 200, 16, 100, 32, 8, 4, 12, 100, 32),
+    (1, 18, 31, 16, 14, 14, 7, 1, 1, 30, 0),            # grid smaller than the input
+    (2, 40, 300, 4, 140, 56, 28, 2, 5, 2000, 0),        # vectors far beyond the frame: clamped references
+    (1, 270, 480, 4, 112, 112, 7, 16, 16, 90, 0),
+    (1, 90, 4200, 8, 1288, 28, 28, 1, 46, 300, 0),      # more than 256 chunks per row
+    (5, 30, 64, 4, 64, 32, 4, 8, 16, 24, 0),            # patch columns exactly four pixels wide
+]
+
+
+@pytest.mark.parametrize("case", range(len(RESIDUAL_CASES)))
+def test_residual_proxy(cs, case):
+    """Per-patch residual scores equal the oracle's bit for bit (integer sums, exact division)."""
+    from oracle import residual_oracle as ro
+    n_frames, h, w, cell, in_w, in_h, patch, gh, gw, spread, pad = RESIDUAL_CASES[case]
+    say(f"residual_proxy case {case}: {n_frames} frames {w}x{h} cell {cell} -> grid {gh}x{gw}")
+    rng = np.random.default_rng(9000 + case)
+    cur = rng.integers(0, 256, size=(n_frames, h, w), dtype=np.uint8)
+    prev = rng.integers(0, 256, size=(n_frames, h, w), dtype=np.uint8)
+    field = rng.integers(-spread, spread + 1, size=(n_frames, -(-h // cell), -(-w // cell), 2)).astype(np.int16)
+    field[:, 0, 0] = (32767, -32768)
+    want = ro.residual_proxy(cur, prev, field, cell, in_w, in_h, patch, gh, gw)
+    got = _residual_gpu(cs, cur, prev, field, cell, in_w, in_h, patch, gh, gw, pad)
+    assert np.array_equal(got, want)
+
+
+def test_residual_proxy_closed_forms_on_gpu(cs):
+    """Exact translation scores 0 everywhere; a constant offset k scores 256 k; no frames is fine."""
+    say("residual_proxy closed forms")
+    rng = np.random.default_rng(9100)
+    h, w = 48, 96
+    prev = rng.integers(0, 200, size=(1, h, w), dtype=np.uint8)
+    ys, xs = np.meshgrid(np.arange(h), np.arange(w), indexing="ij")
+    cur = prev[:, np.clip(ys - 2, 0, h - 1), np.clip(xs + 3, 0, w - 1)]
+    field = np.zeros((1, h // 4, w // 4, 2), np.int16)
+    field[..., 0], field[..., 1] = 12, -8
+    assert not _residual_gpu(cs, cur, prev, field, 4, 48, 24, 8, 3, 6).any()
+    field[:] = 0
+    assert np.all(_residual_gpu(cs, prev + 9, prev, field, 4, 48, 24, 8, 3, 6) == 256 * 9)
+    assert _residual_gpu(cs, cur[:0], prev[:0], field[:0], 4, 48, 24, 8, 3, 6).shape == (0, 18)
+
+
+def test_residual_proxy_feeds_rescue(cs):
+    """Decoder-shaped inputs (1920x1080 planes, macroblock partitions) -> projection + residual
+    proxy -> scoring with residual rescue on, HIP chain against oracle chain."""
+    from oracle import projection_oracle as po
+    from oracle import residual_oracle as ro
+    w = synth.small_variant(synth.CFG2, n_streams=2)
+    say(f"projection + residual proxy -> scoring: {w.name}")
+    src_w, src_h = synth.SOURCE_SIZE
+    in_w, in_h = synth.input_size(w)
+    metas = [synth.stream_metadata(w, s) for s in range(w.n_streams)]
+    ftype = np.concatenate([m.frame_type[-w.stride:] for m in metas])
+    blob = np.concatenate([m.blob[-w.stride:] for m in metas])
+    ftype[:] = 0                                              # P-frames, so that the metadata decides
+    blocks, cu = synth.block_frames(w, ftype, blob)
+    field = synth.motion_field(blocks, cu, 4)
+    cur, prev = synth.decoded_frames(w, ftype.size, blob)
+    geom = (src_w, src_h, in_w, in_h, synth.MODEL_PATCH, w.grid_h, w.grid_w)
+    mv_w, intra_w = po.project_blocks(blocks.view(po.BLOCK_DTYPE), cu, *geom)
+    res_w = ro.residual_proxy(cur, prev, field, 4, in_w, in_h, synth.MODEL_PATCH, w.grid_h, w.grid_w)
+    mv_g, intra_g = _project_gpu(cs, blocks, cu, geom)
+    res_g = _residual_gpu(cs, cur, prev, field, 4, in_w, in_h, synth.MODEL_PATCH, w.grid_h, w.grid_w)
+    assert np.array_equal(res_g, res_w) and np.array_equal(mv_g, mv_w)
+    tau_res = int(0.05 * 255 * 256)                           # 5 % of full scale, in 1/256 grey levels
+    cu_frames = (np.arange(w.n_streams + 1) * w.stride).astype(np.int32)
+    acc = np.zeros((w.n_streams, w.patches), np.uint8)
+    want = oc.score_compact(mv_w, res_w, intra_w, ftype, cu_frames, acc.copy(), w.grid_h, w.grid_w, w.group,
+                            w.tau_mv_sq, tau_res, True)
+    got = _score_gpu(cs, mv_g, res_g, intra_g, ftype, cu_frames, acc.copy(), w.grid_h, w.grid_w, w.group,
+                     w.tau_mv_sq, tau_res, True)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[2], want[2])
+    no_rescue = oc.score_compact(mv_w, None, intra_w, ftype, cu_frames, acc.copy(), w.grid_h, w.grid_w, w.group,
+                                 w.tau_mv_sq, 0, False)
+    say(f"  kept {want[1].size} tokens with rescue, {no_rescue[1].size} without, of {ftype.size * w.tokens_per_frame}")
+    assert want[1].size > no_rescue[1].size
+
+
 # =============================================================================== (b) re-rotation
 def _pool(rng, shape, dtype):
     x = torch.from_numpy(rng.normal(size=shape).astype(np.float32))
