@@ -165,6 +165,39 @@ def block_projection(w, torch, binding, reps):
     return out
 
 
+def residual_proxy(w, torch, binding, reps):
+    """cs_residual_proxy on 1920 x 1080 luma planes with a 4 x 4-pixel motion field: real shape = one
+    new frame per stream (at most 32 streams drawn), scaled = the same planes repeated until current
+    + previous frames exceed 256 MB."""
+    import numpy as np
+    from paper_2604_06036_amd import synth
+    src_w, src_h = synth.SOURCE_SIZE
+    in_w, in_h = synth.input_size(w)
+    n_real = min(w.n_streams * w.stride, 32)
+    metas = [synth.stream_metadata(w, s) for s in range(min(w.n_streams, n_real))]
+    ftype = np.concatenate([m.frame_type[-w.stride:] for m in metas])[:n_real]
+    blob = np.concatenate([m.blob[-w.stride:] for m in metas])[:n_real]
+    blocks, cu = synth.block_frames(w, ftype, blob)
+    field = torch.from_numpy(synth.motion_field(blocks, cu, 4)).cuda()
+    cur, prev = (torch.from_numpy(a).cuda() for a in synth.decoded_frames(w, n_real, blob))
+    out = {}
+    for label in ("real shape", "scaled batch"):
+        n_frames = int(cur.shape[0])
+        res = torch.empty((n_frames, w.patches), dtype=torch.int32, device="cuda")
+        call = lambda: binding.cs_residual_proxy(cur, prev, field, n_frames, src_w, src_h, src_w, src_w * src_h, 4,
+                                                 in_w, in_h, synth.MODEL_PATCH, w.grid_h, w.grid_w, res)
+        for _ in range(2):
+            call()
+        ms = event_time(torch, call, reps)
+        nbytes = n_frames * (2 * src_w * src_h + field.shape[1] * field.shape[2] * 4 + w.patches * 4)
+        out[label] = dict(frames=n_frames, ms=ms, bytes=nbytes, GBps=nbytes / ms / 1e6,
+                          frac_of_hbm_peak=nbytes / ms / 1e6 / PEAK_HBM_GBS)
+        if label == "real shape":
+            rep = max(1, -(-(160 << 20) // (n_frames * src_w * src_h)))
+            cur, prev, field = cur.repeat(rep, 1, 1), prev.repeat(rep, 1, 1), field.repeat(rep, 1, 1, 1)
+    return out
+
+
 def axes_rerotation(w, step, torch, binding, b_bytes, reps):
     """cs_kv_rerotate_axes (three-axis RoPE correction) on the step's own reuse plan: the window
     slides in time only, so the shift is (delta, 0, 0); frequency pairs are mapped to (t, h, w) in
@@ -422,6 +455,7 @@ def main():
     if not args.no_scaled_scoring:
         out["score_compact_scaled"] = scaled_scoring(w, torch, binding)
         out["block_projection"] = block_projection(w, torch, binding, reps)
+        out["residual_proxy"] = residual_proxy(w, torch, binding, reps)
         out["kv_rerotate_axes"] = axes_rerotation(w, step, torch, binding, work["b_bytes"], reps)
     if not args.no_device_plan:
         out["device_planned_step"] = device_planned(w, data, torch, engine, args.steps, args.warmup)

@@ -6,13 +6,15 @@
 // Three launches on the caller's stream; the output array doubles as the accumulator:
 //   1. clear the per-patch sums;
 //   2. residual_sum_kernel: a workgroup owns a run of source rows inside one patch row of one
-//      frame.  A thread owns a 16-pixel column chunk and walks down the rows: one 16-byte load of
-//      the current frame, per 4-pixel group one vector of the motion field, and the reference
-//      pixels as two aligned dwords joined by a byte funnel shift (per-pixel clamped byte loads
-//      only where the reference leaves the frame).  |a - b| over four pixels is one v_sad_u8; a
-//      group that straddles a patch border is split by byte masks fixed per thread, so the row
-//      loop has no patch arithmetic at all.  Sums go thread -> LDS (per patch column) -> one
-//      global atomic per workgroup and patch;
+//      frame.  A thread owns a 4-pixel group of columns (consecutive lanes, consecutive groups:
+//      every load of a wave is one contiguous span) and walks down the rows a cell row of the
+//      motion field at a time: one vector, then for four pixel rows at once the current pixels
+//      (one dword) and the reference pixels as two aligned dwords joined by a byte funnel shift
+//      (per-pixel clamped byte loads only where the reference leaves the frame), twelve
+//      independent loads in flight.  |a - b| over four pixels is one v_sad_u8; a group that
+//      straddles a patch border is split by byte masks fixed per thread, so the row loop has no
+//      patch arithmetic at all.  Sums go thread -> LDS (per patch column) -> one global atomic
+//      per workgroup and patch;
 //   3. residual_mean_kernel: sum -> floor(256 * sum / pixels of the patch).
 // Integer adds commute, so the result is bit exact whatever the order.
 #include "common.h"
@@ -80,73 +82,70 @@ __global__ __launch_bounds__(256) void residual_sum_kernel(ResidualParams p) {
   __syncthreads();
 
   const int W = p.src_w, H = p.src_h;
-  const int chunks = (W + 15) / 16;
-  const int tpr = chunks <= 64 ? 64 : chunks <= 128 ? 128 : 256;     // threads along a row
-  const int phase = tid / tpr, phases = 256 / tpr;
+  const int groups = (W + 3) / 4;                                    // 4-pixel groups along a row
   const uint8_t* cur = p.cur + static_cast<int64_t>(frame) * p.frame_stride;
   const uint8_t* prev = p.prev + static_cast<int64_t>(frame) * p.frame_stride;
   const uint32_t* field = p.field + static_cast<int64_t>(frame) * p.cells_h * p.cells_w;
+  const int cell = 1 << p.cell_shift;
 
-  for (int k = tid % tpr; k < chunks; k += tpr) {
-    // ---- per 4-pixel group: its patch column(s) and the byte masks that split it between them
-    int col_a[4], col_b[4];
-    uint32_t mask_a[4], mask_b[4], acc_a[4], acc_b[4];
+  for (int k = tid; k < groups; k += 256) {
+    // ---- the group's patch column(s) and the byte masks that split it between them
+    const int x = 4 * k;
+    int col_a = static_cast<int>(div_by(static_cast<uint32_t>(x) * p.in_w, p.div_x)), col_b = 0;
+    uint32_t mask_a = 0u, mask_b = 0u;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int x = 16 * k + 4 * g;
-      acc_a[g] = acc_b[g] = 0u;
-      mask_a[g] = mask_b[g] = 0u;
-      col_a[g] = col_b[g] = 0;
-      if (x < W) {
-        const int ca = static_cast<int>(div_by(static_cast<uint32_t>(x) * p.in_w, p.div_x));
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          if (x + t >= W) break;
-          const int c = static_cast<int>(div_by(static_cast<uint32_t>(x + t) * p.in_w, p.div_x));
-          if (c == ca) mask_a[g] |= 0xffu << (8 * t);
-          else { mask_b[g] |= 0xffu << (8 * t); col_b[g] = c; }   // columns are at least 4 pixels wide: one other column at most
-        }
-        col_a[g] = ca;
-        if (ca >= p.grid_w) mask_a[g] = 0u;
-        if (col_b[g] >= p.grid_w) mask_b[g] = 0u;
+    for (int t = 0; t < 4; ++t) {
+      if (x + t < W) {
+        const int c = static_cast<int>(div_by(static_cast<uint32_t>(x + t) * p.in_w, p.div_x));
+        if (c == col_a) mask_a |= 0xffu << (8 * t);
+        else { mask_b |= 0xffu << (8 * t); col_b = c; }     // columns are at least 4 pixels wide: one other column at most
       }
     }
-    // ---- down the rows
-    for (int y = y_begin + phase; y < y_end; y += phases) {
-      const cs::u32x4 c16 = __builtin_nontemporal_load(reinterpret_cast<const cs::u32x4*>(cur + static_cast<int64_t>(y) * p.pitch + 16 * k));
-      const uint32_t cur4[4] = {c16.x, c16.y, c16.z, c16.w};
-      const uint32_t* frow = field + static_cast<int64_t>(y >> p.cell_shift) * p.cells_w;
+    if (col_a >= p.grid_w) mask_a = 0u;
+    if (col_b >= p.grid_w) mask_b = 0u;
+    uint32_t acc_a = 0u, acc_b = 0u;
+    // ---- down the rows, one cell row of the motion field at a time, four pixel rows per batch
+    for (int yc = y_begin >> p.cell_shift; (yc << p.cell_shift) < y_end; ++yc) {
+      const uint32_t mv = field[static_cast<int64_t>(yc) * p.cells_w + (x >> p.cell_shift)];
+      const int ox = (static_cast<int>(static_cast<int16_t>(mv & 0xffffu)) + 2) >> 2;
+      const int oy = (static_cast<int>(static_cast<int16_t>(mv >> 16)) + 2) >> 2;
+      const int xs = x + ox;
+      const bool fast = xs >= 0 && xs + 3 <= W - 1;         // the reference group lies inside the row
+      const int a0 = fast ? (xs & ~3) : 0;                   // two aligned dwords, both inside the row
+      const int a1 = fast && (xs & 3) ? a0 + 4 : a0;
+      for (int r4 = 0; r4 < cell; r4 += 4) {
+        uint32_t c4[4], lo[4], hi[4];
+        bool live[4];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int x = 16 * k + 4 * g;
-        if (x >= W) continue;
-        const uint32_t mv = frow[x >> p.cell_shift];
-        const int ox = (static_cast<int>(static_cast<int16_t>(mv & 0xffffu)) + 2) >> 2;
-        const int oy = (static_cast<int>(static_cast<int16_t>(mv >> 16)) + 2) >> 2;
-        const int yy = min(max(y + oy, 0), H - 1);
-        const uint8_t* prow = prev + static_cast<int64_t>(yy) * p.pitch;
-        const int xs = x + ox;
-        uint32_t pred;
-        if (xs >= 0 && xs + 3 <= W - 1) {
-          // two aligned dwords (both inside the row: xs + 3 < W and the pitch is a multiple of 16)
-          const int a = xs & ~3;
-          const uint32_t lo = *reinterpret_cast<const uint32_t*>(prow + a);
-          const uint32_t hi = (xs & 3) ? *reinterpret_cast<const uint32_t*>(prow + a + 4) : 0u;
-          pred = __builtin_amdgcn_alignbyte(hi, lo, static_cast<uint32_t>(xs & 3));
-        } else {
-          pred = 0u;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) pred |= static_cast<uint32_t>(prow[min(max(xs + t, 0), W - 1)]) << (8 * t);
+        for (int dy = 0; dy < 4; ++dy) {
+          const int y = (yc << p.cell_shift) + r4 + dy;
+          live[dy] = y >= y_begin && y < y_end;
+          const int yv = min(max(y, y_begin), y_end - 1);    // a row of this workgroup in any case
+          const int yy = min(max(yv + oy, 0), H - 1);
+          const uint8_t* prow = prev + static_cast<int64_t>(yy) * p.pitch;
+          c4[dy] = *reinterpret_cast<const uint32_t*>(cur + static_cast<int64_t>(yv) * p.pitch + x);
+          lo[dy] = *reinterpret_cast<const uint32_t*>(prow + a0);
+          hi[dy] = *reinterpret_cast<const uint32_t*>(prow + a1);
         }
-        acc_a[g] = __builtin_amdgcn_sad_u8(cur4[g] & mask_a[g], pred & mask_a[g], acc_a[g]);
-        acc_b[g] = __builtin_amdgcn_sad_u8(cur4[g] & mask_b[g], pred & mask_b[g], acc_b[g]);
+#pragma unroll
+        for (int dy = 0; dy < 4; ++dy) {
+          uint32_t pred = __builtin_amdgcn_alignbyte(hi[dy], lo[dy], static_cast<uint32_t>(xs & 3));
+          if (!fast) {                                       // reference leaves the frame: clamp per pixel
+            const int y = (yc << p.cell_shift) + r4 + dy;
+            const int yv = min(max(y, y_begin), y_end - 1);
+            const uint8_t* prow = prev + static_cast<int64_t>(min(max(yv + oy, 0), H - 1)) * p.pitch;
+            pred = 0u;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) pred |= static_cast<uint32_t>(prow[min(max(xs + t, 0), W - 1)]) << (8 * t);
+          }
+          const uint32_t ma = live[dy] ? mask_a : 0u, mb = live[dy] ? mask_b : 0u;
+          acc_a = __builtin_amdgcn_sad_u8(c4[dy] & ma, pred & ma, acc_a);
+          acc_b = __builtin_amdgcn_sad_u8(c4[dy] & mb, pred & mb, acc_b);
+        }
       }
     }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      if (acc_a[g]) atomicAdd(&s_sum[col_a[g]], acc_a[g]);
-      if (acc_b[g]) atomicAdd(&s_sum[col_b[g]], acc_b[g]);
-    }
+    if (acc_a) atomicAdd(&s_sum[col_a], acc_a);
+    if (acc_b) atomicAdd(&s_sum[col_b], acc_b);
   }
   __syncthreads();
   uint32_t* out = p.res + (static_cast<int64_t>(frame) * p.grid_h + band) * p.grid_w;
@@ -212,7 +211,7 @@ extern "C" int cs_residual_proxy(const uint8_t* cur, const uint8_t* prev, const 
   const int64_t bands = static_cast<int64_t>(n_frames) * grid_h;
   const int64_t band_rows = (static_cast<int64_t>(p.den_y) + in_h - 1) / in_h + 1;
   int64_t n_sub = (2048 + bands - 1) / bands;
-  if (n_sub > band_rows) n_sub = band_rows;
+  if (n_sub > band_rows / 4) n_sub = band_rows / 4;          // rows are walked four at a time
   if (n_sub < 1) n_sub = 1;
   p.n_sub = static_cast<int32_t>(n_sub);
   if (bands * n_sub >= (1ll << 31)) return CS_EUNSUPPORTED;
