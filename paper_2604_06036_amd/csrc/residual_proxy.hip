@@ -73,10 +73,13 @@ __global__ __launch_bounds__(256) void residual_sum_kernel(ResidualParams p) {
   const int frame = blockIdx.x / (p.n_sub * p.grid_h);
   const int y_lo = first_coord(band, p.den_y, p.in_h, p.src_h);
   const int y_hi = first_coord(band + 1, p.den_y, p.in_h, p.src_h);
-  const int rows = y_hi - y_lo;
-  const int y_begin = y_lo + static_cast<int>(static_cast<int64_t>(rows) * sub / p.n_sub);
-  const int y_end = y_lo + static_cast<int>(static_cast<int64_t>(rows) * (sub + 1) / p.n_sub);
-  if (y_begin >= y_end) return;                             // uniform for the workgroup
+  if (y_lo >= y_hi) return;                                 // uniform for the workgroup
+  // the band's rows in quads (rows 4q .. 4q+3, the unit of the row loop), dealt to its n_sub workgroups
+  const int q_lo = y_lo >> 2, n_quads = ((y_hi - 1) >> 2) + 1 - q_lo;
+  const int q_begin = q_lo + static_cast<int>(static_cast<int64_t>(n_quads) * sub / p.n_sub);
+  const int q_end = q_lo + static_cast<int>(static_cast<int64_t>(n_quads) * (sub + 1) / p.n_sub);
+  const int y_begin = max(y_lo, 4 * q_begin), y_end = min(y_hi, 4 * q_end);
+  if (y_begin >= y_end) return;
 
   for (int i = tid; i < p.grid_w; i += 256) s_sum[i] = 0u;
   __syncthreads();
@@ -105,8 +108,12 @@ __global__ __launch_bounds__(256) void residual_sum_kernel(ResidualParams p) {
     if (col_b >= p.grid_w) mask_b = 0u;
     uint32_t acc_a = 0u, acc_b = 0u;
     // ---- down the rows, one cell row of the motion field at a time, four pixel rows per batch
-    for (int yc = y_begin >> p.cell_shift; (yc << p.cell_shift) < y_end; ++yc) {
-      const uint32_t mv = field[static_cast<int64_t>(yc) * p.cells_w + (x >> p.cell_shift)];
+    const int yc_last = (y_end - 1) >> p.cell_shift;
+    const uint32_t* fcol = field + (x >> p.cell_shift);
+    uint32_t mv_next = fcol[static_cast<int64_t>(y_begin >> p.cell_shift) * p.cells_w];
+    for (int yc = y_begin >> p.cell_shift; yc <= yc_last; ++yc) {
+      const uint32_t mv = mv_next;
+      mv_next = fcol[static_cast<int64_t>(min(yc + 1, yc_last)) * p.cells_w];     // one cell row ahead
       const int ox = (static_cast<int>(static_cast<int16_t>(mv & 0xffffu)) + 2) >> 2;
       const int oy = (static_cast<int>(static_cast<int16_t>(mv >> 16)) + 2) >> 2;
       const int xs = x + ox;
@@ -123,7 +130,7 @@ __global__ __launch_bounds__(256) void residual_sum_kernel(ResidualParams p) {
           const int yv = min(max(y, y_begin), y_end - 1);    // a row of this workgroup in any case
           const int yy = min(max(yv + oy, 0), H - 1);
           const uint8_t* prow = prev + static_cast<int64_t>(yy) * p.pitch;
-          c4[dy] = *reinterpret_cast<const uint32_t*>(cur + static_cast<int64_t>(yv) * p.pitch + x);
+          c4[dy] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(cur + static_cast<int64_t>(yv) * p.pitch + x));
           lo[dy] = *reinterpret_cast<const uint32_t*>(prow + a0);
           hi[dy] = *reinterpret_cast<const uint32_t*>(prow + a1);
         }
@@ -210,8 +217,8 @@ extern "C" int cs_residual_proxy(const uint8_t* cur, const uint8_t* prev, const 
   // enough workgroups to fill the chip: split a patch row's source rows among n_sub workgroups
   const int64_t bands = static_cast<int64_t>(n_frames) * grid_h;
   const int64_t band_rows = (static_cast<int64_t>(p.den_y) + in_h - 1) / in_h + 1;
-  int64_t n_sub = (2048 + bands - 1) / bands;
-  if (n_sub > band_rows / 4) n_sub = band_rows / 4;          // rows are walked four at a time
+  int64_t n_sub = (8192 + bands - 1) / bands;               // a few rounds of workgroups per CU
+  if (n_sub > band_rows / 16) n_sub = band_rows / 16;        // at least four quads of rows each: the per-thread set-up is paid once per workgroup
   if (n_sub < 1) n_sub = 1;
   p.n_sub = static_cast<int32_t>(n_sub);
   if (bands * n_sub >= (1ll << 31)) return CS_EUNSUPPORTED;
