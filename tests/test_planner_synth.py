@@ -242,3 +242,56 @@ def test_pipeline_equals_full_causal_attention_over_the_new_window():
     # sizes of this configuration: anchor frame (256) + pruned new frame + 16 text tokens
     n_anchor = sum(1 for kk in plan["q_kind"] if kk == 0)
     assert n_anchor == 256 and sum(1 for kk in plan["q_kind"] if kk == 2) == 16
+
+
+# ------------------------------------------------------------------ decoder-shaped inputs
+def test_block_generator_tiles_the_source_frame_exactly_once():
+    """Every source pixel of a coded frame lies in exactly one block; records have the C layout;
+    I-frames are all intra; the draw is seeded."""
+    w = synth.small_variant(synth.CFG2, n_streams=1)
+    m = synth.stream_metadata(w, 0)
+    ftype = np.array([synth.FRAME_P, synth.FRAME_I], np.uint8)
+    blocks, cu = synth.block_frames(w, ftype, m.blob[-2:])
+    again, cu2 = synth.block_frames(w, ftype, m.blob[-2:])
+    assert blocks.dtype.itemsize == 16 and np.array_equal(blocks, again) and np.array_equal(cu, cu2)
+    src_w, src_h = synth.SOURCE_SIZE
+    for f in range(2):
+        b = blocks[cu[f]:cu[f + 1]]
+        cover = np.zeros(((src_h + 15) // 16 * 16, src_w), np.int32)
+        for size in np.unique(np.stack([b["w"], b["h"]], axis=1), axis=0):
+            sel = b[(b["w"] == size[0]) & (b["h"] == size[1])]
+            for oy in range(int(size[1])):
+                for ox in range(int(size[0])):
+                    np.add.at(cover, (sel["y"] + oy, sel["x"] + ox), 1)
+        assert cover.min() == 1 and cover.max() == 1
+    assert np.all(blocks[cu[1]:cu[2]]["flags"] == 1)                      # the I-frame
+    p = blocks[cu[0]:cu[1]]
+    assert 0 < (p["flags"] == 1).mean() < 0.05 and np.all(p["dx"][p["flags"] == 1] == 0)
+    assert 10_000 < p.size < 20_000
+
+
+def test_motion_field_repeats_the_block_vectors():
+    w = synth.small_variant(synth.CFG2, n_streams=1)
+    m = synth.stream_metadata(w, 0)
+    blocks, cu = synth.block_frames(w, m.frame_type[-1:] * 0, m.blob[-1:])
+    field = synth.motion_field(blocks, cu, 4)
+    src_w, src_h = synth.SOURCE_SIZE
+    assert field.shape == (1, src_h // 4, src_w // 4, 2)
+    rng = np.random.default_rng(5)
+    for i in rng.integers(0, blocks.size, size=200):
+        b = blocks[i]
+        y, x = int(b["y"]) // 4, int(b["x"]) // 4
+        if y < field.shape[1]:
+            want = (0, 0) if b["flags"] else (int(b["dx"]), int(b["dy"]))
+            assert tuple(field[0, y, x]) == want
+
+
+def test_decoded_frames_are_seeded_and_differ_where_the_scene_changes():
+    w = synth.small_variant(synth.CFG2, n_streams=1)
+    m = synth.stream_metadata(w, 0)
+    cur, prev = synth.decoded_frames(w, 1, m.blob[-1:])
+    cur2, prev2 = synth.decoded_frames(w, 1, m.blob[-1:])
+    assert cur.shape == (1, 1080, 1920) and cur.dtype == np.uint8
+    assert np.array_equal(cur, cur2) and np.array_equal(prev, prev2)
+    diff = np.abs(cur[0].astype(int) - prev[0].astype(int))
+    assert 1.0 < diff.mean() < 40.0 and np.median(diff) <= 2
