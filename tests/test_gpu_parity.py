@@ -128,6 +128,21 @@ def test_score_compact_waves_sweeping_several_streams(cs):
     _score_case(cs, rng, 20011, list(rng.integers(0, 3, 20011)), 8, 8, 1, 300, 1000, True, True, False)
 
 
+@pytest.mark.parametrize("n_streams,grid,group,max_frames", [
+    (4097, (16, 16), 1, 2),        # just past the one-launch limit, packed lanes
+    (5003, (4, 6), 2, 3),          # token groups of 2 x 2 patches
+    (6001, (3, 5), 1, 2),          # patch count not a multiple of 4: one location per lane and group
+    (4100, (20, 20), 1, 3),        # 400 token locations: two sweeps per frame
+])
+def test_score_compact_three_launch_form(cs, n_streams, grid, group, max_frames):
+    """Batches above 4096 streams run as score / scan / emit launches: every variant of the kernel
+    body in that form, ragged frame counts (streams without frames included)."""
+    say(f"score_compact three-launch form: {n_streams} streams, grid {grid}, group {group}")
+    rng = np.random.default_rng(90 + n_streams)
+    _score_case(cs, rng, n_streams, list(rng.integers(0, max_frames + 1, n_streams)), grid[0], grid[1], group,
+                200, 900, True, True, True)
+
+
 def test_score_compact_i_frame_ignores_metadata(cs):
     say("score_compact: garbage in I-frame metadata")
     rng = np.random.default_rng(3)
