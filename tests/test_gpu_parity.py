@@ -1112,3 +1112,52 @@ def test_graph_replay_matches_eager(cs):
         got = snapshot()
         for i, (a, b) in enumerate(zip(eager, got)):
             assert torch.equal(a, b), f"replay {rep}: tensor {i} differs from the eager result"
+
+
+def test_graph_replay_of_the_device_planned_step(cs):
+    """The step with the refresh plan made on the GPU, captured in a HIP graph: every replay gives
+    the eager results (plan lists, totals, cache, attention), with the plan's output arrays and the
+    workspaces dirtied between replays."""
+    w = synth.small_variant(synth.CFG2, n_streams=3, n_layers=2)
+    say(f"graph replay, device-planned step: {w.name}, 3 streams, 2 layers, 3 replays")
+    data = engine.assemble_step(w, engine.hip_scorer, device="cpu")
+    n_reuse, n_q = data.info["n_reuse"], data.info["n_q"]
+    step = engine.DevicePlannedStep(data, reuse_cap=n_reuse + 200, q_cap=n_q + 200)
+    k0, v0 = step.k_pool.clone(), step.v_pool.clone()
+    names = ("keep", "kept_off", "src_slot", "dst_slot", "delta", "q_pos", "q_slot", "q_kind", "cu_q", "kv_len",
+             "totals", "new_types_out", "new_counts_out", "k_pool", "v_pool", "out")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [getattr(step, n).clone() for n in names]
+
+    def dirty():
+        step.k_pool.copy_(k0); step.v_pool.copy_(v0)
+        step.out.zero_()
+        for n in ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "cu_q", "kv_len", "totals", "kept_off"):
+            getattr(step, n).fill_(-5)
+        step.q_kind.fill_(9)
+        step.ws_p.random_(0, 255)
+        step.ws_a.random_(0, 255)
+
+    step.run()
+    eager = snapshot()
+    assert eager[names.index("totals")].cpu().tolist() == [n_reuse, n_q, 0, 0]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dirty()
+        step.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step.run()
+    for rep in range(3):
+        dirty()
+        scratch = torch.randn(1 << 20, device=DEV).sum().item()      # eager work between replays
+        assert math.isfinite(scratch)
+        graph.replay()
+        got = snapshot()
+        for n, a, b in zip(names, eager, got):
+            assert torch.equal(a, b), f"replay {rep}: {n} differs from the eager result"
