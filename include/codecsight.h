@@ -229,7 +229,9 @@ int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intr
  *  totals                  out  int32 [4]: reused rows, executed rows, flags (1: reused rows exceed
  *                          reuse_cap, 2: executed rows exceed q_cap, 4: a sequence index falls
  *                          outside its block-table row), 0.  Rows beyond a capacity are not
- *                          written; a row whose slot cannot be formed gets slot -1.
+ *                          written and cu_q is clamped to q_cap (the streams that do not fit lose
+ *                          their last executed rows), so the consumers stay inside the lists
+ *                          whatever the flags say; a row whose slot cannot be formed gets slot -1.
  *  workspace               cs_plan_refresh_workspace() bytes, 16-byte aligned, contents need not
  *                          be initialised
  * All pointers are device memory.  Bit exact (integer work).

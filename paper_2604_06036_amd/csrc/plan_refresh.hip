@@ -55,6 +55,7 @@ struct PlanRefreshParams {
   int32_t* __restrict__ st_q;                // [B] executed rows of the stream (text included)
   int32_t* __restrict__ st_head;             // [B] kept tokens of the frames that left the window
   int32_t* __restrict__ reuse_base;          // [B]
+  int32_t* __restrict__ q_base;              // [B] first executed row of the stream (cu_q before clamping)
 };
 
 __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
@@ -139,14 +140,18 @@ __global__ __launch_bounds__(kScanThreads) void plan_streams_kernel(PlanRefreshP
     for (int w = 0; w < wave; ++w) { base_r += part_r[w]; base_q += part_q[w]; }
     if (s < p.n_streams) {
       p.reuse_base[s] = base_r + r_inc - r;
-      p.cu_q[s] = base_q + q_inc - q;
+      const int first_q = base_q + q_inc - q;
+      p.q_base[s] = first_q;
+      // what the consumers see never points past the capacity: rows that do not fit are dropped
+      // (and flagged), the rows that do are where cu_q says
+      p.cu_q[s] = static_cast<int>(min(static_cast<int64_t>(first_q), p.q_cap));
     }
     __syncthreads();
     if (tid == kScanThreads - 1) { run_r = base_r + r_inc; run_q = base_q + q_inc; }
     __syncthreads();
   }
   if (tid == 0) {
-    p.cu_q[p.n_streams] = run_q;
+    p.cu_q[p.n_streams] = static_cast<int>(min(static_cast<int64_t>(run_q), p.q_cap));
     p.totals[0] = run_r;
     p.totals[1] = run_q;
     p.totals[2] = (run_r > p.reuse_cap ? kFlagReuseCap : 0) | (run_q > p.q_cap ? kFlagQueryCap : 0);
@@ -198,7 +203,7 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanRefreshParams p, int
       }
     }
   } else {
-    const int64_t o0 = static_cast<int64_t>(p.cu_q[s]) + r.y;
+    const int64_t o0 = static_cast<int64_t>(p.q_base[s]) + r.y;
     for (int i = lane; i < cnt; i += 64) {
       const int64_t o = o0 + i;
       const int dst = slot_of(btn, p.max_blocks_new, seq0 + i, &bad);
@@ -215,7 +220,7 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanRefreshParams p, int
 inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct PlanRefreshLayout {
-  size_t off_rec, off_reuse, off_q, off_head, off_base, total;
+  size_t off_rec, off_reuse, off_q, off_head, off_base, off_qbase, total;
 };
 
 PlanRefreshLayout layout_for(int64_t n_streams, int64_t window) {
@@ -226,6 +231,7 @@ PlanRefreshLayout layout_for(int64_t n_streams, int64_t window) {
   l.off_q = at;        at = align256(at + static_cast<size_t>(n_streams) * sizeof(int32_t));
   l.off_head = at;     at = align256(at + static_cast<size_t>(n_streams) * sizeof(int32_t));
   l.off_base = at;     at = align256(at + static_cast<size_t>(n_streams) * sizeof(int32_t));
+  l.off_qbase = at;    at = align256(at + static_cast<size_t>(n_streams) * sizeof(int32_t));
   l.total = at;
   return l;
 }
@@ -296,6 +302,7 @@ extern "C" int cs_plan_refresh(const uint8_t* old_types, const int32_t* old_coun
   p.st_q = reinterpret_cast<int32_t*>(w + l.off_q);
   p.st_head = reinterpret_cast<int32_t*>(w + l.off_head);
   p.reuse_base = reinterpret_cast<int32_t*>(w + l.off_base);
+  p.q_base = reinterpret_cast<int32_t*>(w + l.off_qbase);
 
   hipStream_t st = cs::as_stream(stream);
   if (n_streams > 0) {
