@@ -231,13 +231,16 @@ int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intr
  *                          outside its block-table row), 0.  Rows beyond a capacity are not
  *                          written and cu_q is clamped to q_cap (the streams that do not fit lose
  *                          their last executed rows), so the consumers stay inside the lists
- *                          whatever the flags say; a row whose slot cannot be formed gets slot -1.
+ *                          whatever the flags say; a row whose slot cannot be formed gets slot -1
+ *                          (and an executed row's q_pos is pulled back to the last position its
+ *                          block-table row covers, so attention never indexes past the table).
  *  workspace               cs_plan_refresh_workspace() bytes, 16-byte aligned, contents need not
  *                          be initialised
  * All pointers are device memory.  Bit exact (integer work).
  * Errors: CS_EINVAL (null pointer, negative size, window < 1, stride outside 1..window,
- *         tokens_per_frame < 1), CS_EUNSUPPORTED (n_streams*(window+1), a capacity or
- *         stride*tokens_per_frame >= 2^31), CS_EWORKSPACE, CS_EHIP.
+ *         tokens_per_frame < 1, a block table without columns), CS_EUNSUPPORTED
+ *         (n_streams*(window+1), a capacity or stride*tokens_per_frame >= 2^31), CS_EWORKSPACE,
+ *         CS_EHIP.
  * ------------------------------------------------------------------------------------------ */
 size_t cs_plan_refresh_workspace(int32_t n_streams, int32_t window);
 

@@ -208,7 +208,9 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanRefreshParams p, int
       const int64_t o = o0 + i;
       const int dst = slot_of(btn, p.max_blocks_new, seq0 + i, &bad);
       if (o < p.q_cap) {
-        p.q_pos[o] = seq0 + i;
+        // a position the block-table row does not cover (flagged) is pulled back onto the row, so
+        // that attention queued behind this plan never indexes past the table
+        p.q_pos[o] = dst < 0 ? min(seq0 + i, p.max_blocks_new * CS_KV_BLOCK - 1) : seq0 + i;
         p.q_slot[o] = dst;
         p.q_kind[o] = static_cast<uint8_t>(kind);
       }
@@ -256,6 +258,7 @@ extern "C" int cs_plan_refresh(const uint8_t* old_types, const int32_t* old_coun
   if (n_streams < 0 || window < 1 || stride < 1 || stride > window || n_text < 0 || tokens_per_frame < 1)
     return CS_EINVAL;
   if (max_blocks_old < 0 || max_blocks_new < 0 || reuse_cap < 0 || q_cap < 0) return CS_EINVAL;
+  if (n_streams > 0 && (max_blocks_old < 1 || max_blocks_new < 1)) return CS_EINVAL;
   if (!cu_q || !totals) return CS_EINVAL;
   if (n_streams > 0 && (!old_types || !old_counts || !new_types || !kept_off || !block_table_old ||
                         !block_table_new || !kv_len || !out_types || !out_counts))

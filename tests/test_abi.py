@@ -127,6 +127,7 @@ def test_host_side_argument_errors(lib):
     assert plan(t=0) == binding.CS_EINVAL
     assert plan(nt_=-1) == binding.CS_EINVAL
     assert plan(rc=-1) == binding.CS_EINVAL
+    assert plan(mbn=0) == binding.CS_EINVAL
     assert plan(ot=z) == binding.CS_EINVAL
     assert plan(ko=z) == binding.CS_EINVAL
     assert plan(src=z) == binding.CS_EINVAL
