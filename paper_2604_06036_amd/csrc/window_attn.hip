@@ -635,8 +635,15 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
       const int n_wg = min(pp.n_slots, 64);
       int load = lane < n_wg ? 0 : 0x7fffffff;          // half key tiles; lanes beyond the grid rank last
       int last = -1, first3[3] = {-1, -1, -1}, taken = 0;
-      for (int base = begin; base < end; base += n_wg) {
-        const int n_here = min(n_wg, end - base);
+      // (a pair-ordered list that is not a whole number of batches starts with the short batch:
+      // the full batches that follow even the loads out again, which a short batch at the end
+      // cannot.  A list ordered by length keeps its batches aligned instead: workgroups that start
+      // equal-length items together sweep the same key ranges together and share them in L2,
+      // which is worth more there: 6 % on the dense long-window case.)
+      int n_batch = grouped ? (end - begin) % n_wg : 0;
+      if (n_batch == 0) n_batch = n_wg;
+      for (int base = begin; base < end; base += n_batch, n_batch = n_wg) {
+        const int n_here = min(n_batch, end - base);      // the last batch of a length-ordered list may be short
         int len = -1;                                     // lanes without an item rank last
         if (lane < n_here) {
           const int kbe = __hip_atomic_load(&pp.items[static_cast<int64_t>(base + lane) * 8 + 5], __ATOMIC_RELAXED,
