@@ -604,6 +604,102 @@ def _attn_case(cs, rng, dtype, n_q_heads, n_kv_heads, d, kv_lens, n_qs, shuffle=
     return hp.check_attention(out[:n_q].cpu(), ref, dtype)
 
 
+PLAN_HDR_INTS = 32 + 32 * 8 * 64        # list offsets, row-tile count, end item; then one 32-int entry per (XCD, workgroup)
+
+
+def _attention_plan(cs, cu, q_pos, kv_lens, bt, hq, hkv):
+    """Runs the planning launch alone and returns (header ints, item descriptors [n, 8])."""
+    n_streams, max_blocks, n_q = len(kv_lens), int(bt.shape[1]), int(q_pos.size)
+    d = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).astype(dt)).to(DEV)
+    wsb = cs.cs_window_prefill_attn_workspace(n_q, n_streams, hq, hkv, 128, max_blocks, cs.CS_BF16)
+    ws = torch.randint(0, 255, (wsb,), dtype=torch.uint8, device=DEV)
+    cs.cs_window_prefill_attn(None, None, None, d(cu, np.int32), d(q_pos, np.int32), d(kv_lens, np.int32), d(bt, np.int32),
+                              max_blocks, 16, None, n_q, n_streams, hq, hkv, 128, hkv * 128, 128, 0.1, cs.CS_BF16, ws, wsb,
+                              cs.CS_ATTN_PLAN_ONLY)
+    torch.cuda.synchronize()
+    hdr = ws[: PLAN_HDR_INTS * 4].view(torch.int32).cpu().numpy()
+    off = (PLAN_HDR_INTS * 4 + 255) // 256 * 256
+    n_items = int(hdr[8])
+    items = ws[off: off + n_items * 32].view(torch.int32).cpu().numpy().reshape(n_items, 8)
+    return hdr, items
+
+
+@pytest.mark.parametrize("hq,hkv,kv_lens,n_qs", [
+    (28, 4, [915], [425]),                                              # one stream, sweeps split over keys
+    (32, 8, [300, 1, 640, 77], [100, 1, 333, 0]),                       # lists dealt by pair, short batches
+    (8, 1, [513], [70]),
+    (28, 4, [6033], [300]),
+    (8, 2, [3000, 700, 40], [257, 64, 40]),
+    (2, 1, [20] * 2100, [2] * 2100),
+    (28, 4, [300 + 7 * i for i in range(40)], [60 + i for i in range(40)]),     # more items than workgroups
+    (28, 4, [1100 + 13 * i for i in range(32)], [380 + 5 * i for i in range(32)]),
+])
+def test_attention_plan_is_a_valid_schedule(cs, hq, hkv, kv_lens, n_qs):
+    """The planning launch alone (nothing computed, nothing that could fault on a bad schedule): the
+    items cover every (stream, kv head, row tile) and its key tiles exactly once, every item lies on
+    exactly one workgroup's chain inside its XCD's list, and each workgroup's header entry agrees
+    with its chain.  Runs before the attention tests, which trust the plan."""
+    say(f"attention plan: heads={hq}/{hkv} streams={len(kv_lens)} rows={sum(n_qs) * (hq // hkv)}")
+    rng = np.random.default_rng(4000 + len(kv_lens) + sum(n_qs))
+    g = hq // hkv
+    nb = [-(-L // 16) for L in kv_lens]
+    bt = np.zeros((len(kv_lens), max(nb) + 1), np.int32)
+    ids, at = rng.permutation(sum(nb) + 3), 0
+    for s in range(len(kv_lens)):
+        bt[s, : nb[s]] = ids[at: at + nb[s]]
+        at += nb[s]
+    q_pos, cu = [], [0]
+    for s in range(len(kv_lens)):
+        q_pos.append(np.sort(rng.choice(kv_lens[s], size=n_qs[s], replace=False)) if n_qs[s] else np.zeros(0, int))
+        cu.append(cu[-1] + n_qs[s])
+    q_pos = np.concatenate(q_pos).astype(np.int64)
+    hdr, items = _attention_plan(cs, np.asarray(cu), q_pos, np.asarray(kv_lens), bt, hq, hkv)
+    lists = hdr[:9]
+    assert lists[0] == 0 and np.all(np.diff(lists) >= 0) and lists[8] == items.shape[0]
+    assert list(hdr[16:24]) == [0, 0, 0, 0, -1, 0, -1, -1]                 # the end item
+    # ---- coverage: key ranges of a row tile's items tile [0, n_kt) exactly
+    ranges = {}
+    for it in items:
+        q0, rows, r_tile, kvh_s, wg_max, kbe = (int(v) for v in it[:6])
+        ranges.setdefault((kvh_s >> 8, kvh_s & 255, r_tile), []).append((kbe & 0xffff, kbe >> 16, q0, rows, wg_max))
+    want = set()
+    for s in range(len(kv_lens)):
+        rows = n_qs[s] * g
+        for t in range(-(-rows // 128)):
+            last = min((t + 1) * 128, rows) - 1
+            wg_max = int(q_pos[cu[s] + last // g])
+            for kvh in range(hkv):
+                want.add((s, kvh, t * 128))
+                segs = sorted(ranges.get((s, kvh, t * 128), []))
+                assert segs, (s, kvh, t)
+                assert all(x[2] == cu[s] and x[3] == rows and x[4] == wg_max for x in segs)
+                assert segs[0][0] == 0 and segs[-1][1] == wg_max // 64 + 1
+                assert all(a[1] == b[0] and a[0] < a[1] for a, b in zip(segs, segs[1:])) and segs[-1][0] < segs[-1][1]
+    assert set(ranges) == want
+    assert hdr[9] == len(want)
+    # ---- chains
+    seen = np.zeros(items.shape[0], bool)
+    for x in range(8):
+        for j in range(64):
+            e = hdr[32 + 32 * (64 * x + j): 32 + 32 * (64 * x + j) + 17]
+            chain, i = [], int(e[0])
+            while i >= 0:
+                assert lists[x] <= i < lists[x + 1] and not seen[i], (x, j, i)
+                seen[i] = True
+                chain.append(i)
+                i = int(items[i, 6])
+            assert int(e[16]) == len(chain) and [int(v) for v in e[:3]] == (chain + [-1, -1, -1])[:3]
+            if chain:
+                first = items[chain[0]]
+                assert np.array_equal(e[8:16], first)
+                row, last_blk, kt0 = bt[int(first[3]) >> 8], int(first[4]) >> 4, int(first[5]) & 0xffff
+                assert int(e[3]) == int(row[last_blk])
+                assert [int(v) for v in e[4:8]] == [int(row[min(kt0 * 4 + i, last_blk)]) for i in range(4)]
+            else:
+                assert list(e[8:16]) == [0, 0, 0, 0, -1, 0, -1, -1]
+    assert seen.all()
+
+
 ATTN_CASES = [
     # dtype, Hq, Hkv, d, kv_lens, n_qs
     ("f32", 2, 1, 64, [452], [332]),
