@@ -49,6 +49,7 @@ struct ScoreParams {
   uint32_t* wave_total;                  // ... followed by the kept tokens per wave
   int32_t n_streams, n_frames, grid_w, tok_w, n_patch, n_tok;
   int32_t streams_per_wave;              // consecutive streams swept by one wave (1 for small batches)
+  int32_t single_tile;                   // one-launch form with one workgroup: no ticket, no look-back, no clearing launch
   uint32_t tau_mv_sq, tau_sad;
   int32_t use_residual;
 };
@@ -366,7 +367,14 @@ __global__ __launch_bounds__(kWavesPerTile * cs::kWave) void score_compact_kerne
   const int lane = threadIdx.x & (cs::kWave - 1);
   const int wave = threadIdx.x / cs::kWave;
   if constexpr (MODE == kFused) {
-    if (threadIdx.x == 0) s_ticket = atomicAdd(p.ticket, 1u);
+    if (threadIdx.x == 0) {
+      if (p.single_tile) {
+        s_ticket = 0;
+        *p.error = 0;                    // the word callers may inspect; nothing else of the workspace is used
+      } else {
+        s_ticket = atomicAdd(p.ticket, 1u);
+      }
+    }
     __syncthreads();
   }
   const uint32_t tile = MODE == kFused ? s_ticket : blockIdx.x;
@@ -454,7 +462,7 @@ __global__ __launch_bounds__(kWavesPerTile * cs::kWave) void score_compact_kerne
       uint32_t aggregate = 0;
 #pragma unroll
       for (int w = 0; w < kWavesPerTile; ++w) aggregate += s_total[w];
-      const uint32_t exclusive = look_back(p, tile, aggregate, lane);
+      const uint32_t exclusive = p.single_tile ? 0u : look_back(p, tile, aggregate, lane);
       if (lane == 0) s_exclusive = exclusive;
     }
     __syncthreads();
@@ -612,7 +620,8 @@ extern "C" int cs_score_compact(const int16_t* mv, const uint32_t* sad, const ui
   p.use_residual = use_residual ? 1 : 0;
   p.streams_per_wave = split ? sp.streams_per_wave : streams_per_wave_for(n_streams);
 
-  if (!split) {                                             // ticket + error word, tile states
+  p.single_tile = !split && n_tiles == 1 ? 1 : 0;
+  if (!split && n_tiles > 1) {                              // ticket + error word, tile states
     const int n_words = n_tiles + 1;
     hipLaunchKernelGGL(clear_words_kernel, dim3((n_words + 255) / 256), dim3(256), 0, st,
                        reinterpret_cast<uint64_t*>(workspace), n_words);
