@@ -67,12 +67,11 @@ const char* cs_version(void);
 int cs_last_hip_error(void);
 
 /* ------------------------------------------------------------------------------------------
- * (m) Block-to-patch projection.     Paper Sec. 3.3.1 ("Mapping codec changes to ViT patches":
- *     every coding block's footprint in the source frame is projected onto the patch grid of the
- *     preprocessed model input with the frame-to-input scaling, and a patch receives the largest
- *     motion-vector magnitude, Eq. 1, among the blocks whose projected footprints overlap it);
- *     Sec. 3.3.2 (patches overlapping intra-coded regions are retained).  Produces the `mv` and
- *     `intra` inputs of cs_score_compact from a decoder's per-block output.
+ * (m) Block-to-patch projection.     Paper Sec. 3.3.1, paragraph on mapping codec changes to ViT
+ *     patches: block rectangles live in source-frame pixels, patches in model-input pixels; the
+ *     rectangles are rescaled and every patch is given the strongest motion (Eq. 1) found among
+ *     the blocks that land on it.  Sec. 3.3.2: a patch touched by an intra-coded block is kept.
+ *     Produces the `mv` and `intra` inputs of cs_score_compact from a decoder's per-block output.
  *
  * Block m covers source pixels [x, x+w) x [y, y+h), clipped to the src_w x src_h frame; its image
  * is [x sx, (x+w) sx) x [y sy, (y+h) sy) with sx = in_w/src_w, sy = in_h/src_h (a plain resize).
@@ -109,8 +108,8 @@ int cs_project_blocks(const cs_block* blocks, const int32_t* cu_blocks, int32_t 
 
 /* ------------------------------------------------------------------------------------------
  * (r) Residual proxy.     Paper Sec. 4, "Codec Processing" (the decoder exposes no prediction
- *     residuals; each patch's residual score is the mean absolute difference from the
- *     motion-compensated prediction of the previous decoded frame); it stands in for the block
+ *     residuals; a patch is scored by how far its pixels are, on average and in absolute value,
+ *     from the previous decoded frame displaced by the motion vectors); it stands in for the block
  *     residual of Eq. 2 and feeds the rescue rule of Eq. 4.  Produces the `sad` input of
  *     cs_score_compact.
  *
@@ -156,8 +155,8 @@ int cs_residual_proxy(const uint8_t* cur, const uint8_t* prev, const int16_t* mv
  *               d     = d_mv | d_res | (intra && intra[i] != 0)      (Eq. 5)
  *             acc[i] |= d (GOP accumulation; with acc_mask == NULL the patch mask is d itself),
  *             a token is kept when any patch of its group x group block is selected.
- * Kept tokens of all frames are then listed in frame-major, row-major order ("selected
- * embeddings retain their original relative order").
+ * Kept tokens of all frames are then listed in frame-major, row-major order (the selection keeps
+ * the tokens' original relative order, Sec. 3.3.2).
  *
  * Thresholds are integers in the metadata's own units, so the mask is exact: a threshold of
  * tau pixels on quarter-pel vectors is tau_mv_sq = (4*tau)^2; a strict '>' is '>= value+1'.
@@ -257,7 +256,7 @@ int cs_plan_refresh(const uint8_t* old_types, const int32_t* old_counts,
 
 /* ------------------------------------------------------------------------------------------
  * (b) Position-corrected reuse of cached keys.          Paper Sec. 3.4.2, Eq. 6; Sec. 3.5
- *     ("repacking reusable states into the destination KV cache").
+ *     (reusable states are repacked into the destination cache of the current request).
  *
  * For every reused row r, every layer l < n_layers and every kv head h:
  *     K[l][dst_slot[r]][h] = R(delta[r]) * K[l][src_slot[r]][h]
@@ -287,9 +286,9 @@ int cs_kv_rerotate(void* k_cache, void* v_cache,
                    float rope_base, int32_t rope_style, int32_t dtype, void* stream);
 
 /* ------------------------------------------------------------------------------------------
- * (b') The same correction for multidimensional RoPE.       Paper Sec. 3.4.2 (after Eq. 6: "for
- *     multidimensional RoPE, the correction follows the model's mapping from positional
- *     components to rotary dimensions"); Sec. 4 names Qwen3-VL's three-axis mRoPE.
+ * (b') The same correction for multidimensional RoPE.       Paper Sec. 3.4.2 (after Eq. 6: with
+ *     several positional components, each rotary dimension is corrected by the component the
+ *     model maps to it); Sec. 4 names Qwen3-VL's three-axis mRoPE.
  *
  * A position is a triple (t, h, w).  Frequency pair i of a head (the same pairs and the same
  * theta_i = rope_base^(-2i/head_dim) as in cs_kv_rerotate) is driven by positional component
@@ -309,8 +308,8 @@ int cs_kv_rerotate_axes(void* k_cache, void* v_cache,
                         float rope_base, int32_t rope_style, int32_t dtype, void* stream);
 
 /* ------------------------------------------------------------------------------------------
- * (c) In-place refresh write.                            Paper Sec. 3.5 ("newly computed K/V are
- *     written directly into the destination cache before causal attention is evaluated").
+ * (c) In-place refresh write.                            Paper Sec. 3.5 (at each layer the K/V
+ *     just computed go straight into the destination cache, before attention runs).
  *
  * One layer:  K[slot[i]][h] = k_new[i][h],  V[slot[i]][h] = v_new[i][h]  for slot[i] >= 0;
  * a negative slot skips the token.  Pure data movement, bit exact.
@@ -328,8 +327,8 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
 
 /* ------------------------------------------------------------------------------------------
  * (d) Joint prefill attention of refresh + suffix tokens over the mixed cache.   Paper Sec. 3.5
- *     ("attention reads a combination of reused states and states computed in the current pass,
- *     allowing suffix tokens to attend to refreshed anchors").
+ *     (attention reads reused states and states of the current pass side by side, so the suffix
+ *     sees the refreshed anchors).
  *
  * One layer, n_streams streams in one variable-length launch.  Stream s owns query rows
  * cu_q[s] .. cu_q[s+1]-1; query t sits at window-sequence index q_pos[t] and sees cache entries

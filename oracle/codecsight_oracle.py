@@ -142,8 +142,8 @@ def rerotate(k_cache, v_cache, src_slot, dst_slot, delta, base, style=0):
 
 
 def rotate_axes(x, pos3, axis_of_pair, base, style=0):
-    """Multidimensional RoPE (Sec. 3.4.2: "the correction follows the model's mapping from
-    positional components to rotary dimensions").  A position is a triple (t, h, w); frequency
+    """Multidimensional RoPE (Sec. 3.4.2: each rotary dimension is corrected by the positional
+    component the model maps to it).  A position is a triple (t, h, w); frequency
     pair i, with the same theta_i as 1-D RoPE, is driven by component axis_of_pair[i]:
 
         angle_i = pos3[..., axis_of_pair[i]] * theta_i

@@ -1,14 +1,13 @@
 """CPU oracle of the block-to-patch projection -- TEST INFRASTRUCTURE ONLY.
 
-Sec. 3.3.1 of the CodecSight paper, "Mapping codec changes to ViT patches": codec signals live on
-coding blocks of the source frame, the vision encoder works on a patch grid of the preprocessed
-model input; every block's footprint is projected onto that grid with the frame-to-input scaling
-and a patch takes the largest motion magnitude (Eq. 1) among the blocks whose projected footprint
-overlaps it.  Sec. 3.3.2: a patch that overlaps an intra-coded region carries the intra flag.
+Sec. 3.3.1 of the CodecSight paper (the paragraph on mapping codec changes to ViT patches): block
+rectangles are given in source-frame pixels, patches in model-input pixels; rescale the rectangles
+and give every patch the strongest motion (Eq. 1) found among the blocks that land on it.
+Sec. 3.3.2: a patch touched by an intra-coded block carries the intra flag.
 
 Written as the definition: for every patch, test every block for overlap, take the maximum.
 Geometry is exact (integer cross-multiplication, no floating point).  Shares nothing with the HIP
-path.  Pinned in tests/test_oracle_pins.py by hand-worked examples (tests/golden/), a brute-force
+path.  Pinned in tests/test_projection_pins.py by hand-worked examples (tests/golden/), a brute-force
 painter on a fine common grid, aligned-geometry special cases and invariants.
 
 Readings (the paper leaves them open):

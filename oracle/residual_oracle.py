@@ -1,10 +1,9 @@
 """CPU oracle of the residual proxy -- TEST INFRASTRUCTURE ONLY.
 
-Sec. 4 ("Codec Processing") of the CodecSight paper: the hardware decoder does not expose
-prediction residuals, so a reconstruction-error proxy is computed from decoded frames and motion
-vectors: a patch's residual score is the mean absolute difference between the frame and the
-motion-compensated prediction formed from the previous decoded frame (the per-patch counterpart of
-the block residual of Eq. 2, used by the rescue rule of Eq. 4).
+Sec. 4 (Codec Processing) of the CodecSight paper: the hardware decoder hands out no residuals, so
+they are approximated from pixels: shift the previous decoded frame by the motion vectors, compare
+it with the current frame, and score a patch by the average absolute pixel difference inside it
+(the per-patch counterpart of the block residual of Eq. 2, used by the rescue rule of Eq. 4).
 
 Written as the definition: build the prediction pixel by pixel, take absolute differences, average
 over the pixels of each patch.  Integers throughout.  Shares nothing with the HIP path.  Pinned in

@@ -16,8 +16,8 @@
 // digits in float); sin/cos of the reduced angle (single-precision minimax polynomials with the
 // Cephes sinf/cosf coefficients), the products and the final rounding are single precision.
 //
-// Multidimensional RoPE (Sec. 3.4.2: "the correction follows the model's mapping from positional
-// components to rotary dimensions"): a row's shift is a triple (d_t, d_h, d_w) and frequency pair i
+// Multidimensional RoPE (Sec. 3.4.2: each rotary dimension is corrected by the positional
+// component the model maps to it): a row's shift is a triple (d_t, d_h, d_w) and frequency pair i
 // is driven by component axis_of_pair[i]; everything else is the same kernel (template flag).
 #include <math.h>
 

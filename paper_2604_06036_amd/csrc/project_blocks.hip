@@ -1,7 +1,7 @@
-// Block-to-patch projection.  Paper Sec. 3.3.1 ("Mapping codec changes to ViT patches"): codec
-// signals are defined on coding blocks of the source frame, the encoder works on a patch grid of
-// the preprocessed input; a patch takes the largest motion magnitude (Eq. 1) among the blocks whose
-// projected footprint overlaps it.  Sec. 3.3.2: patches overlapping intra-coded regions are flagged.
+// Block-to-patch projection.  Paper Sec. 3.3.1 (paragraph on mapping codec changes to ViT
+// patches): block rectangles are in source-frame pixels, patches in model-input pixels; the
+// rectangles are rescaled and every patch gets the strongest motion (Eq. 1) among the blocks that
+// land on it.  Sec. 3.3.2: a patch touched by an intra-coded block is flagged.
 //
 // One workgroup per frame.  The frame's patch table lives in LDS as 64-bit keys
 //     key = |v|^2 << 32 | (dx + 32768) << 16 | (dy + 32768)

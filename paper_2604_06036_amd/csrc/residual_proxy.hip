@@ -1,7 +1,7 @@
-// Residual proxy.  Paper Sec. 4 ("Codec Processing"): the decoder exposes no prediction
-// residuals, so a patch's residual score is the mean absolute difference between the decoded frame
-// and the motion-compensated prediction formed from the previous decoded frame (the per-patch
-// counterpart of the block residual of Eq. 2; input of the rescue rule, Eq. 4).
+// Residual proxy.  Paper Sec. 4 (Codec Processing): the decoder hands out no residuals, so they
+// are approximated from pixels: the previous decoded frame is shifted by the motion vectors,
+// compared with the current frame, and a patch is scored by the average absolute pixel difference
+// inside it (the per-patch counterpart of the block residual of Eq. 2; input of the rescue rule, Eq. 4).
 //
 // Three launches on the caller's stream; the output array doubles as the accumulator:
 //   1. clear the per-patch sums;
