@@ -298,3 +298,175 @@ class DevicePlannedStep(DeviceStep):
         for layer in range(self.data.workload.n_layers):
             self.refresh_scatter(layer)
             self.attention(layer, reuse_plan=layer > 0)
+
+
+@dataclass
+class FrontEndData:
+    """Inputs of a slide step that starts from decoder output: coding blocks, a motion field and
+    the decoded luma planes of the S new frames of every stream (stream-major), the cached window,
+    block tables sized for the largest window the step can produce, and capacity-sized Q/K/V."""
+    workload: synth.Workload
+    blocks: np.ndarray                 # synth.BLOCK_DTYPE records
+    cu_blocks: np.ndarray              # int32 [F+1]
+    field: np.ndarray                  # int16 [F, H/4, W/4, 2]
+    cur: np.ndarray                    # uint8 [F, H, W]
+    prev: np.ndarray
+    frame_type: np.ndarray             # uint8 [F]
+    cu_frames: np.ndarray              # int32 [B+1]
+    acc_in: np.ndarray                 # uint8 [B, P]
+    old_layout: planner.WindowLayout
+    bt_new: np.ndarray                 # int32 [B, max_blocks]
+    n_slots: int
+    reuse_cap: int
+    q_cap: int
+    tau_res: int
+    k_pool: object = None
+    v_pool: object = None
+    q: object = None
+    k_new: object = None
+    v_new: object = None
+    softmax_scale: float = 0.0
+
+
+def assemble_frontend_step(w: synth.Workload, scorer: Scorer, device="cpu", tau_res: Optional[int] = None) -> FrontEndData:
+    """The cached window comes from scoring the history as in `assemble_step`; the S new frames
+    arrive as decoder output.  How many of their tokens survive is only known on the device, so
+    block tables, pool and the executed-row capacity allow for every token of a new frame."""
+    meta = synth.batch_metadata(w)
+    n_streams, hist, stride, window, t_per = w.n_streams, w.history, w.stride, w.window, w.tokens_per_frame
+    past = hist - stride
+    rows = meta.rows(0, past)
+    cu = (np.arange(n_streams + 1) * past).astype(np.int32)
+    _, _, off_h, acc_h = scorer(meta.mv[rows], meta.sad[rows], meta.frame_type[rows], cu,
+                                np.zeros((n_streams, w.patches), np.uint8), w, w.tau_mv_sq, w.tau_sad)
+    counts_h = np.diff(off_h).reshape(n_streams, past)
+    old_counts = counts_h[:, past - window:].astype(np.int32)
+    old_types = meta.frame_type.reshape(n_streams, hist)[:, past - window: past].astype(np.uint8)
+    rows_new = meta.rows(past, stride)
+    ftype = meta.frame_type[rows_new]
+    blob = np.concatenate([synth.stream_metadata(w, s).blob[past:] for s in range(n_streams)])
+    blocks, cu_blocks = synth.block_frames(w, ftype, blob)
+    field = synth.motion_field(blocks, cu_blocks, 4)
+    cur, prev = synth.decoded_frames(w, int(ftype.shape[0]), blob)
+
+    overlap_types, overlap_counts = old_types[:, stride:], old_counts[:, stride:]
+    old_len = old_counts.sum(axis=1) + w.n_text
+    new_len_max = overlap_counts.sum(axis=1) + stride * t_per + w.n_text
+    nb_old, nb_new = planner.blocks_needed(old_len), planner.blocks_needed(new_len_max)
+    ids = synth.block_ids(w, int(nb_old.sum() + nb_new.sum()), tag=1)
+    bt_old = np.zeros((n_streams, int(nb_old.max())), np.int32)
+    bt_new = np.zeros((n_streams, int(nb_new.max())), np.int32)
+    at = 0
+    for s in range(n_streams):
+        bt_old[s, : nb_old[s]] = ids[at: at + nb_old[s]]
+        at += int(nb_old[s])
+        bt_new[s, : nb_new[s]] = ids[at: at + nb_new[s]]
+        at += int(nb_new[s])
+    n_slots = int(ids.shape[0]) * synth.KV_BLOCK
+    reused = int(overlap_counts[overlap_types != synth.FRAME_I].sum())
+    anchors = int(overlap_counts[overlap_types == synth.FRAME_I].sum())
+    q_cap = anchors + n_streams * (stride * t_per + w.n_text)
+    data = FrontEndData(w, blocks, cu_blocks, field, cur, prev, ftype, (np.arange(n_streams + 1) * stride).astype(np.int32),
+                        acc_h, planner.WindowLayout(old_types, old_counts, w.n_text, bt_old), bt_new, n_slots,
+                        reused, q_cap, int(0.05 * 255 * 256) if tau_res is None else int(tau_res),
+                        softmax_scale=1.0 / math.sqrt(w.head_dim))
+    shape_pool = (w.n_layers, n_slots, w.n_kv_heads, w.head_dim)
+    data.k_pool = synth.normal_tensor(w, (11,), shape_pool, device)
+    data.v_pool = synth.normal_tensor(w, (12,), shape_pool, device)
+    data.q = synth.normal_tensor(w, (13,), (w.n_layers, q_cap, w.n_q_heads, w.head_dim), device)
+    data.k_new = synth.normal_tensor(w, (14,), (w.n_layers, q_cap, w.n_kv_heads, w.head_dim), device)
+    data.v_new = synth.normal_tensor(w, (15,), (w.n_layers, q_cap, w.n_kv_heads, w.head_dim), device)
+    return data
+
+
+class FrontEndStep:
+    """The whole chain on the GPU, queued without a host round trip: block projection and residual
+    proxy (decoder output -> per-patch metadata), scoring + compaction, refresh plan, position
+    correction of the reused rows, then per layer refresh write and attention."""
+
+    def __init__(self, data: FrontEndData):
+        import torch
+        from . import binding as cs
+        self.cs, self.data = cs, data
+        w = data.workload
+        dev = self.dev = torch.device("cuda")
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        self.dtype = cs.CS_BF16 if w.dtype == "bf16" else cs.CS_F32
+        self.n_frames = int(data.frame_type.shape[0])
+        self.src_w, self.src_h = synth.SOURCE_SIZE
+        self.in_w, self.in_h = synth.input_size(w)
+        self.blocks = to(data.blocks.view(np.uint8))
+        self.n_blocks = int(data.blocks.shape[0])
+        self.cu_blocks, self.field, self.cur, self.prev = to(data.cu_blocks), to(data.field), to(data.cur), to(data.prev)
+        self.frame_type, self.cu_frames = to(data.frame_type), to(data.cu_frames)
+        self.acc, self.acc_in = to(data.acc_in), to(data.acc_in)
+        i32 = lambda shape, fill=0: torch.full(shape, fill, dtype=torch.int32, device=dev)
+        self.mv = torch.zeros((self.n_frames, w.patches, 2), dtype=torch.int16, device=dev)
+        self.intra = torch.zeros((self.n_frames, w.patches), dtype=torch.uint8, device=dev)
+        self.res = i32((self.n_frames, w.patches))
+        t_per = w.tokens_per_frame
+        self.keep = torch.zeros((self.n_frames, t_per), dtype=torch.uint8, device=dev)
+        self.kept_idx, self.kept_off = i32((self.n_frames * t_per,)), i32((self.n_frames + 1,))
+        self.ws_a_bytes = cs.cs_score_compact_workspace(w.n_streams, self.n_frames, w.grid_h, w.grid_w, w.group)
+        self.ws_a = torch.zeros((max(8, self.ws_a_bytes),), dtype=torch.uint8, device=dev)
+        old = data.old_layout
+        self.old_types, self.old_counts = to(old.frame_type), to(old.counts)
+        self.bt_old, self.bt_new = to(old.block_table), to(data.bt_new)
+        self.max_blocks_old, self.max_blocks = int(old.block_table.shape[1]), int(data.bt_new.shape[1])
+        self.reuse_cap, self.q_cap = data.reuse_cap, data.q_cap
+        self.src_slot, self.dst_slot, self.delta = (i32((max(1, self.reuse_cap),), -9) for _ in range(3))
+        self.q_pos, self.q_slot = i32((self.q_cap,), -9), i32((self.q_cap,), -9)
+        self.q_kind = torch.full((self.q_cap,), 7, dtype=torch.uint8, device=dev)
+        self.cu_q, self.kv_len, self.totals = i32((w.n_streams + 1,)), i32((w.n_streams,)), i32((4,))
+        self.new_types, self.new_counts = torch.zeros_like(self.old_types), torch.zeros_like(self.old_counts)
+        self.ws_p_bytes = cs.cs_plan_refresh_workspace(w.n_streams, w.window)
+        self.ws_p = torch.zeros((max(8, self.ws_p_bytes),), dtype=torch.uint8, device=dev)
+        self.k_pool, self.v_pool = data.k_pool.to(dev), data.v_pool.to(dev)
+        self.stride_layer, self.stride_slot, self.stride_head = (self.k_pool.stride(i) for i in range(3))
+        self.q, self.k_new, self.v_new = data.q.to(dev), data.k_new.to(dev), data.v_new.to(dev)
+        self.out = torch.zeros_like(self.q)
+        self.ws_d_bytes = cs.cs_window_prefill_attn_workspace(self.q_cap, w.n_streams, w.n_q_heads, w.n_kv_heads,
+                                                              w.head_dim, self.max_blocks, self.dtype)
+        self.ws_d = torch.zeros((max(8, self.ws_d_bytes),), dtype=torch.uint8, device=dev)
+
+    def front_end(self):
+        w, cs = self.data.workload, self.cs
+        cs.cs_project_blocks(self.blocks, self.cu_blocks, self.n_frames, self.src_w, self.src_h, self.in_w, self.in_h,
+                             synth.MODEL_PATCH, w.grid_h, w.grid_w, self.mv, self.intra, n_blocks=self.n_blocks)
+        cs.cs_residual_proxy(self.cur, self.prev, self.field, self.n_frames, self.src_w, self.src_h, self.src_w,
+                             self.src_w * self.src_h, 4, self.in_w, self.in_h, synth.MODEL_PATCH, w.grid_h, w.grid_w,
+                             self.res)
+
+    def score_and_plan(self):
+        w, cs = self.data.workload, self.cs
+        self.acc.copy_(self.acc_in)                       # a repeated run plans the same step
+        cs.cs_score_compact(self.mv, self.res, self.intra, self.frame_type, self.cu_frames, self.acc, w.n_streams,
+                            self.n_frames, w.grid_h, w.grid_w, w.group, w.tau_mv_sq, self.data.tau_res, True, self.keep,
+                            self.kept_idx, self.kept_off, self.ws_a, self.ws_a_bytes)
+        cs.cs_plan_refresh(self.old_types, self.old_counts, self.frame_type, self.kept_off, self.bt_old,
+                           self.max_blocks_old, self.bt_new, self.max_blocks, w.n_streams, w.window, w.stride, w.n_text,
+                           w.tokens_per_frame, self.reuse_cap, self.q_cap, self.src_slot, self.dst_slot, self.delta,
+                           self.q_pos, self.q_slot, self.q_kind, self.cu_q, self.kv_len, self.new_types, self.new_counts,
+                           self.totals, self.ws_p, self.ws_p_bytes)
+
+    def kv_and_attention(self):
+        w, cs = self.data.workload, self.cs
+        if self.reuse_cap > 0:
+            cs.cs_kv_rerotate(self.k_pool, self.v_pool, self.src_slot, self.dst_slot, self.delta, self.reuse_cap,
+                              w.n_layers, w.n_kv_heads, w.head_dim, self.stride_layer, self.stride_slot, self.stride_head,
+                              w.rope_base, cs.CS_ROPE_HALF_SPLIT, self.dtype)
+        for layer in range(w.n_layers):
+            cs.cs_kv_refresh_scatter(self.k_new[layer], self.v_new[layer], self.q_slot, self.k_pool[layer],
+                                     self.v_pool[layer], self.q_cap, w.n_kv_heads, w.head_dim, self.stride_slot,
+                                     self.stride_head, self.dtype)
+            cs.cs_window_prefill_attn(self.q[layer], self.k_pool[layer], self.v_pool[layer], self.cu_q, self.q_pos,
+                                      self.kv_len, self.bt_new, self.max_blocks, cs.CS_KV_BLOCK, self.out[layer],
+                                      self.q_cap, w.n_streams, w.n_q_heads, w.n_kv_heads, w.head_dim, self.stride_slot,
+                                      self.stride_head, self.data.softmax_scale, self.dtype,
+                                      self.ws_d if self.ws_d_bytes else None, self.ws_d_bytes,
+                                      cs.CS_ATTN_PLAN_REUSE if layer > 0 else cs.CS_ATTN_PLAN_BUILD)
+
+    def run(self):
+        self.front_end()
+        self.score_and_plan()
+        self.kv_and_attention()

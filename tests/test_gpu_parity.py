@@ -1078,6 +1078,80 @@ def test_device_planned_step_equals_host_planned_step(cs, wi, slack):
     assert not devp.out[:, n_q:].any()                           # rows past the executed rows are not written
 
 
+def test_frontend_to_attention_chain_against_oracle_chain(cs):
+    """Decoder output in, attention output out, nothing through the host in between: block
+    projection, residual proxy, scoring with rescue, refresh plan, position correction, and per
+    layer refresh write + attention, queued back to back on capacity-sized lists.  The oracle runs
+    the same chain stage by stage from the same inputs."""
+    from oracle import plan_oracle as plo
+    from oracle import projection_oracle as pjo
+    from oracle import residual_oracle as rso
+    w = synth.small_variant(synth.CFG2, n_streams=2, n_layers=2)
+    say(f"front end -> attention chain: {w.name} streams={w.n_streams} layers={w.n_layers}")
+    data = engine.assemble_frontend_step(w, engine.hip_scorer, device="cpu")
+    data_o = engine.assemble_frontend_step(w, hp.oracle_scorer, device="cpu")
+    assert np.array_equal(data.old_layout.counts, data_o.old_layout.counts) and np.array_equal(data.acc_in, data_o.acc_in)
+    step = engine.FrontEndStep(data)
+    k0, v0 = data.k_pool.clone(), data.v_pool.clone()
+    step.run()
+    torch.cuda.synchronize()
+    # ---- oracle chain
+    src_w, src_h = synth.SOURCE_SIZE
+    in_w, in_h = synth.input_size(w)
+    mv_w, intra_w = pjo.project_blocks(data.blocks.view(pjo.BLOCK_DTYPE), data.cu_blocks, src_w, src_h, in_w, in_h,
+                                       synth.MODEL_PATCH, w.grid_h, w.grid_w)
+    res_w = rso.residual_proxy(data.cur, data.prev, data.field, 4, in_w, in_h, synth.MODEL_PATCH, w.grid_h, w.grid_w)
+    assert np.array_equal(step.mv.cpu().numpy(), mv_w) and np.array_equal(step.intra.cpu().numpy(), intra_w)
+    assert np.array_equal(step.res.cpu().numpy().view(np.uint32), res_w)
+    keep_w, idx_w, off_w, acc_w = oc.score_compact(mv_w, res_w, intra_w, data.frame_type, data.cu_frames, data.acc_in.copy(),
+                                                   w.grid_h, w.grid_w, w.group, w.tau_mv_sq, data.tau_res, True)
+    assert np.array_equal(step.keep.cpu().numpy(), keep_w) and np.array_equal(step.kept_off.cpu().numpy(), off_w)
+    assert np.array_equal(step.kept_idx.cpu().numpy()[: idx_w.size], idx_w)
+    new_counts = np.diff(off_w).reshape(w.n_streams, w.stride)
+    old = data.old_layout
+    keys = ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "q_kind")
+    cat = {k: [] for k in keys}
+    cu_q, kv_len = [0], []
+    for s in range(w.n_streams):
+        pl = plo.plan_stream(old.frame_type[s].tolist(), old.counts[s].tolist(),
+                             data.frame_type[s * w.stride: (s + 1) * w.stride].tolist(), new_counts[s].tolist(),
+                             w.n_text, w.tokens_per_frame, old.block_table[s], data.bt_new[s])
+        for k in keys:
+            cat[k] += pl[k]
+        cu_q.append(cu_q[-1] + len(pl["q_pos"]))
+        kv_len.append(pl["kv_len"])
+    n_r, n_e = len(cat["src_slot"]), len(cat["q_pos"])
+    say(f"  {data.blocks.size} blocks, kept {idx_w.size} new tokens, {n_r} reused rows, {n_e} executed rows "
+        f"(capacity {data.q_cap})")
+    assert step.totals.cpu().tolist() == [n_r, n_e, 0, 0] and n_r == data.reuse_cap and n_e <= data.q_cap
+    for k in ("src_slot", "dst_slot", "delta"):
+        assert getattr(step, k)[:n_r].cpu().tolist() == cat[k], k
+    for k in ("q_pos", "q_slot", "q_kind"):
+        assert getattr(step, k)[:n_e].cpu().tolist() == cat[k], k
+    assert step.cu_q.cpu().tolist() == cu_q and step.kv_len.cpu().tolist() == kv_len
+    src, dst = np.asarray(cat["src_slot"]), np.asarray(cat["dst_slot"])
+    q_slot, q_pos = np.asarray(cat["q_slot"]), np.asarray(cat["q_pos"], np.int32)
+    delta = np.asarray(cat["delta"])
+    layers = list(range(w.n_layers))
+    k_rows, v_rows = oc.rerotate(hp.f64(k0[layers]), hp.f64(v0[layers]), src, dst, delta, w.rope_base)
+    got_rows = step.k_pool.cpu()[:, torch.from_numpy(dst)].permute(1, 0, 2, 3).contiguous()
+    say(f"  rerotate: {hp.check_rerotated(got_rows, k_rows, w.dtype)}")
+    k_ref, v_ref = k0.clone(), v0.clone()
+    for i, layer in enumerate(layers):
+        k_ref[layer][torch.from_numpy(dst)] = hp.round_like(k_rows[:, i], torch.bfloat16)
+        v_ref[layer][torch.from_numpy(dst)] = hp.round_like(v_rows[:, i], torch.bfloat16)
+        oc.scatter(k_ref[layer].view(torch.int16).numpy(), data.k_new[layer][:n_e].view(torch.int16).numpy(), q_slot)
+        oc.scatter(v_ref[layer].view(torch.int16).numpy(), data.v_new[layer][:n_e].view(torch.int16).numpy(), q_slot)
+    assert torch.equal(step.v_pool.cpu().view(torch.int16), v_ref.view(torch.int16))       # values: bit-exact moves
+    qs = torch.from_numpy(q_slot)
+    assert torch.equal(step.k_pool.cpu()[:, qs].view(torch.int16), data.k_new[:, :n_e].view(torch.int16))
+    for layer in layers:
+        ref = oc.window_attn(hp.f64(data.q[layer][:n_e]), hp.f64(step.k_pool[layer]), hp.f64(step.v_pool[layer]),
+                             np.asarray(cu_q, np.int32), q_pos, data.bt_new, w.n_q_heads, data.softmax_scale)
+        say(f"  attention layer {layer}: {hp.check_attention(step.out[layer][:n_e].cpu(), ref, w.dtype)}")
+    assert not step.out[:, n_e:].any()
+
+
 FULL_WORKLOADS = [synth.CFG1, synth.CFG2, synth.CFG3P, synth.CFG3D, synth.CFG4]
 
 
