@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM counters and copy bandwidth)")
+    ap.add_argument("--no-frontend-step", action="store_true",
+                    help="skip the leg that runs the chain from decoder output to attention output")
     ap.add_argument("--no-device-plan", action="store_true",
                     help="skip the leg that runs the step with the refresh plan made on the GPU")
     ap.add_argument("--no-scaled-scoring", action="store_true",
@@ -269,6 +271,40 @@ def device_planned(w, data, torch, engine, steps, warmup):
                 reuse_cap=step.reuse_cap, q_cap=step.q_cap, host_route_ms=ms_host)
 
 
+def frontend_step(w, torch, engine, steps, warmup):
+    """The chain from decoder output to attention output in one HIP graph: block projection,
+    residual proxy, scoring with rescue, refresh plan on the GPU, position correction, then per
+    layer refresh write + attention, on lists sized to the step's capacities (every token of a new
+    frame may be kept).  Its executed-token count comes from the device plan."""
+    data = engine.assemble_frontend_step(w, engine.hip_scorer, device="cuda")
+    step = engine.FrontEndStep(data)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    totals = step.totals.cpu().tolist()
+    if totals[2] != 0:
+        raise RuntimeError(f"front-end step: plan flags {totals}")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step.run()
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / steps
+    t_front = event_time(torch, step.front_end, max(3, min(steps, 20)))
+    t_plan = event_time(torch, step.score_and_plan, max(3, min(steps, 20)))
+    return dict(ms_per_step=ms, executed_tokens=totals[1], reused_rows=totals[0], q_cap=data.q_cap,
+                tokens_per_s=totals[1] / (ms * 1e-3), front_end_ms=t_front, score_and_plan_ms=t_plan,
+                frames=int(data.frame_type.shape[0]), blocks=int(data.blocks.shape[0]))
+
+
 def cpu_baseline(w, data, step, torch):
     """The oracle, as it stands, on the host: scoring, re-rotation of every reused row for all
     layers, then refresh write + attention for a bounded number of layers, scaled to all layers."""
@@ -457,6 +493,8 @@ def main():
         out["block_projection"] = block_projection(w, torch, binding, reps)
         out["residual_proxy"] = residual_proxy(w, torch, binding, reps)
         out["kv_rerotate_axes"] = axes_rerotation(w, step, torch, binding, work["b_bytes"], reps)
+    if not args.no_frontend_step:
+        out["frontend_step"] = frontend_step(w, torch, engine, args.steps, args.warmup)
     if not args.no_device_plan:
         out["device_planned_step"] = device_planned(w, data, torch, engine, args.steps, args.warmup)
     if not args.no_cpu_baseline:
