@@ -1,16 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the codec-guided window-prefill step on one MI355X.
 
-A "step" is one pass of the whole hot path over one batch of synthetic streams:
-  cs_score_compact -> cs_kv_rerotate (all layers) -> per layer: cs_kv_refresh_scatter,
-  cs_window_prefill_attn.
+A "step" is one pass of the whole hot path over one batch of synthetic streams, with nothing
+passing through the host in between:
+  cs_score_compact -> cs_plan_refresh -> cs_kv_rerotate (all layers) -> per layer:
+  cs_kv_refresh_scatter, cs_window_prefill_attn.
 Inputs are resident in HBM before the timed region starts.  The step is captured once in a HIP
-graph and the timed region replays it K times (the refresh plan is built beforehand from an
-identical, untimed run of the scoring kernel; planning on the host is not part of the timed step).
+graph and the timed region replays it K times.
+
+By default all five bf16 workloads are measured one after the other (the one-stream shape, the
+32-stream batch, both readings of the long window, the 64-stream batch); the top-level `value`,
+`ms_per_step`, `config` and `roofline` are those of the LAST one, the largest (64 streams, 32
+layers), and `workloads` carries the same figures for each.  `--workload NAME` measures one.
 
 Printed: ONE JSON line with the whole-job throughput (executed tokens per second), a `roofline`
-object for the dominant kernel (event-timed on the launch stream) and a `cpu_baseline` object (the
-CPU oracle timed on this machine's host cores on a bounded sample of the same workload).
+object for the dominant kernel (event-timed on the launch stream), per-kernel rooflines, and a
+`cpu_baseline` object (the CPU oracle timed on this machine's host cores on a bounded sample of the
+headline workload, on all cores and on one).
 """
 from __future__ import annotations
 
@@ -26,7 +32,8 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16
-DEFAULT_WORKLOAD = "cfg1_qwen7b_1stream"
+DEFAULT_WORKLOADS = ("cfg1_qwen7b_1stream", "cfg2_qwen7b_32streams", "cfg3p_longwindow_pruned",
+                     "cfg3d_longwindow_dense", "cfg4_internlm7b_64streams")   # the last one is the headline
 
 
 def parse():
@@ -34,18 +41,23 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default=DEFAULT_WORKLOAD,
-                    help="one of the synthetic workloads in paper_2604_06036_amd.synth.WORKLOADS")
+    ap.add_argument("--workload", default=None,
+                    help="measure this workload only (a name in paper_2604_06036_amd.synth.WORKLOADS); "
+                         "default: all five bf16 workloads, the 64-stream batch as the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM counters and copy bandwidth)")
     ap.add_argument("--no-frontend-step", action="store_true",
                     help="skip the leg that runs the chain from decoder output to attention output")
-    ap.add_argument("--no-device-plan", action="store_true",
-                    help="skip the leg that runs the step with the refresh plan made on the GPU")
+    ap.add_argument("--no-host-plan", action="store_true",
+                    help="skip the comparison leg whose refresh plan is made on the host before the timed region")
     ap.add_argument("--no-scaled-scoring", action="store_true",
-                    help="skip the scaled-batch bandwidth measurement of cs_score_compact")
+                    help="skip the scaled-batch legs (cs_score_compact, block projection, residual proxy, "
+                         "three-axis re-rotation)")
+    ap.add_argument("--side-legs-workload", default="cfg2_qwen7b_32streams",
+                    help="the workload whose shapes the side legs (scaled scoring, front end) use when "
+                         "several workloads are measured")
     return ap.parse_args()
 
 
@@ -220,30 +232,18 @@ def axes_rerotation(w, step, torch, binding, b_bytes, reps):
                 sections=[n_t, n_h, half - n_t - n_h])
 
 
-def device_planned(w, data, torch, engine, steps, warmup):
-    """The same step with the refresh plan made on the GPU between scoring and re-rotation
-    (cs_plan_refresh), captured in a HIP graph: nothing passes through the host inside the step.
-    Row lists are sized to capacities 1/8 above the step's row counts, rounded up to 256; the
-    consumers run over the capacities and skip the padding.  For comparison, the host route the
-    default step keeps outside its timed region: copy the offsets back, plan on the host, copy the
-    lists to the device."""
-    import numpy as np
-    from paper_2604_06036_amd import planner
-    cap = lambda n: (n + n // 8 + 255) // 256 * 256
-    info = data.info
-    step = engine.DevicePlannedStep(data, reuse_cap=cap(info["n_reuse"]), q_cap=cap(info["n_q"]))
+def graph_time(torch, run, steps, warmup):
+    """Captures run() in a HIP graph (after one eager run on a side stream) and returns the wall
+    milliseconds per replay over `steps` replays that follow `warmup` untimed ones."""
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        step.run()
+        run()
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
-    totals = step.totals.cpu().tolist()
-    if totals != [info["n_reuse"], info["n_q"], 0, 0]:
-        raise RuntimeError(f"device plan totals {totals} differ from the host plan's")
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        step.run()
+        run()
     for _ in range(warmup):
         graph.replay()
     torch.cuda.synchronize()
@@ -251,8 +251,14 @@ def device_planned(w, data, torch, engine, steps, warmup):
     for _ in range(steps):
         graph.replay()
     torch.cuda.synchronize()
-    ms_step = 1e3 * (time.perf_counter() - t0) / steps
-    t_plan = event_time(torch, step.plan_refresh, max(3, min(steps, 20)))
+    return 1e3 * (time.perf_counter() - t0) / steps, graph
+
+
+def host_route_time(w, data, step, torch):
+    """Wall time of the host route that cs_plan_refresh replaces: copy the offsets back, plan on
+    the host, copy the lists to the device (test-side planner; not part of any timed step)."""
+    import numpy as np
+    from paper_2604_06036_amd import planner
 
     def host_route():
         off = step.kept_off.cpu().numpy()                                   # waits for the scoring call
@@ -266,9 +272,7 @@ def device_planned(w, data, torch, engine, steps, warmup):
     t0 = time.perf_counter()
     for _ in range(5):
         host_route()
-    ms_host = 1e3 * (time.perf_counter() - t0) / 5
-    return dict(ms_per_step=ms_step, tokens_per_s=info["n_q"] / (ms_step * 1e-3), plan_call_ms=t_plan,
-                reuse_cap=step.reuse_cap, q_cap=step.q_cap, host_route_ms=ms_host)
+    return 1e3 * (time.perf_counter() - t0) / 5
 
 
 def frontend_step(w, torch, engine, steps, warmup):
@@ -278,26 +282,12 @@ def frontend_step(w, torch, engine, steps, warmup):
     frame may be kept).  Its executed-token count comes from the device plan."""
     data = engine.assemble_frontend_step(w, engine.hip_scorer, device="cuda")
     step = engine.FrontEndStep(data)
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        step.run()
-    torch.cuda.current_stream().wait_stream(side)
+    step.run()
     torch.cuda.synchronize()
     totals = step.totals.cpu().tolist()
     if totals[2] != 0:
         raise RuntimeError(f"front-end step: plan flags {totals}")
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        step.run()
-    for _ in range(warmup):
-        graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        graph.replay()
-    torch.cuda.synchronize()
-    ms = 1e3 * (time.perf_counter() - t0) / steps
+    ms, _graph = graph_time(torch, step.run, steps, warmup)
     t_front = event_time(torch, step.front_end, max(3, min(steps, 20)))
     t_plan = event_time(torch, step.score_and_plan, max(3, min(steps, 20)))
     return dict(ms_per_step=ms, executed_tokens=totals[1], reused_rows=totals[0], q_cap=data.q_cap,
@@ -305,57 +295,192 @@ def frontend_step(w, torch, engine, steps, warmup):
                 frames=int(data.frame_type.shape[0]), blocks=int(data.blocks.shape[0]))
 
 
-def cpu_baseline(w, data, step, torch):
-    """The oracle, as it stands, on the host: scoring, re-rotation of every reused row for all
-    layers, then refresh write + attention for a bounded number of layers, scaled to all layers."""
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, data, step, k_rows_before, pick, torch):
+    """The oracle, as it stands, on the host: scoring of the step's frames, re-rotation of a sample
+    of the reused rows (all layers), refresh write + attention of ONE layer on a sample of the
+    executed rows, each scaled to the whole step; once on all host threads and once on one."""
     import numpy as np
     from oracle import codecsight_oracle as oc
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+    from threadpoolctl import threadpool_info, threadpool_limits
+    all_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     p = data.plan
     f64 = lambda t: t.detach().cpu().float().numpy().astype(np.float64)
-    pairs_per_layer = w.n_q_heads * data.info["visible_pairs"]
-    # keep the sample near 10-30 s: the fp64 oracle sustains very roughly 2e9 pair-dims/s per core
-    budget_pairs = 1.0e9 * max(1, cores)
-    n_l = int(max(1, min(w.n_layers, budget_pairs // max(1.0, pairs_per_layer * w.head_dim / 64))))
-    max_rows = 4096
-    rows = p.src_slot.shape[0]
-    pick = np.arange(rows) if rows <= max_rows else np.sort(np.random.default_rng(0).choice(rows, max_rows, replace=False))
-    k_host = step.k_pool_before[:, torch.from_numpy(p.src_slot[pick].astype(np.int64)).to(step.dev)].cpu()
-    t0 = time.perf_counter()
-    oc.score_compact(data.mv, data.sad if w.use_residual else None, None, data.frame_type, data.cu_frames,
-                     data.acc_in, w.grid_h, w.grid_w, w.group, w.tau_mv_sq, w.tau_sad, w.use_residual)
-    t_a = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    oc.rotate(f64(k_host), p.delta[pick].astype(np.float64)[None, :, None], w.rope_base)
-    t_b = (time.perf_counter() - t0) * rows / max(1, pick.size)
-    # layers: cache after (b) is taken as given (copying device results to the host is not timed)
-    q_sel = None
+    rows = int(p.src_slot.shape[0])
     n_q = int(p.q_pos.size)
-    max_q = 2048
-    qrows = None if n_q <= max_q else np.sort(np.random.default_rng(1).choice(n_q, max_q, replace=False))
-    t_cd = 0.0
-    for layer in range(n_l):
-        k_l, v_l = f64(step.k_pool[layer]), f64(step.v_pool[layer])
-        kn, vn, q_l = f64(step.k_new[layer]), f64(step.v_new[layer]), f64(step.q[layer])
+    k_l, v_l = f64(step.k_pool[0]), f64(step.v_pool[0])          # cache of layer 0 after the step (not timed)
+    kn, vn, q_l = f64(step.k_new[0][:n_q]), f64(step.v_new[0][:n_q]), f64(step.q[0][:n_q])
+    k_host = k_rows_before.float().numpy().astype(np.float64)
+
+    def timed(threads, max_q, max_rot):
+        with threadpool_limits(limits=threads):
+            t0 = time.perf_counter()
+            oc.score_compact(data.mv, data.sad if w.use_residual else None, None, data.frame_type, data.cu_frames,
+                             data.acc_in.copy(), w.grid_h, w.grid_w, w.group, w.tau_mv_sq, w.tau_sad, w.use_residual)
+            t_a = time.perf_counter() - t0
+            n_rot = min(max_rot, pick.size)
+            t0 = time.perf_counter()
+            if n_rot:
+                oc.rotate(k_host[:, :n_rot], p.delta[pick[:n_rot]].astype(np.float64)[None, :, None, None], w.rope_base)
+            t_b = (time.perf_counter() - t0) * rows / max(1, n_rot)
+            t0 = time.perf_counter()
+            oc.scatter(k_l, kn, p.q_slot)
+            oc.scatter(v_l, vn, p.q_slot)
+            t_c = time.perf_counter() - t0
+            qrows = None if n_q <= max_q else np.sort(np.random.default_rng(1).choice(n_q, max_q, replace=False))
+            t0 = time.perf_counter()
+            oc.window_attn(q_l, k_l, v_l, p.cu_q, p.q_pos, p.layout.block_table, w.n_q_heads,
+                           data.softmax_scale, rows=qrows)
+            t_d = (time.perf_counter() - t0) * (1.0 if qrows is None else n_q / qrows.size)
+        t_step = t_a + t_b + w.n_layers * (t_c + t_d)
+        return dict(tokens_per_s=n_q / t_step, seconds_per_step=t_step, threads=int(threads),
+                    parts_s=dict(score_compact=t_a, kv_rerotate=t_b, refresh_scatter_per_layer=t_c,
+                                 attention_per_layer=t_d),
+                    queries_sampled=int(min(n_q, max_q)), rotated_rows_sampled=int(min(max_rot, pick.size)))
+
+    multi = timed(all_threads, 4096, 4096)
+    single = timed(1, 512, 512)
+    sample = (f"oracle (NumPy, fp64): scoring of the step's {data.frame_type.shape[0]} frames; re-rotation of "
+              f"{multi['rotated_rows_sampled']} of {rows} reused rows x {w.n_layers} layers; refresh write of all "
+              f"{n_q} rows and attention of {multi['queries_sampled']} of {n_q} executed rows for 1 of {w.n_layers} "
+              f"layers; each part scaled to the whole step (single-thread leg: {single['queries_sampled']} queries, "
+              f"{single['rotated_rows_sampled']} rows)")
+    return dict(value=multi["tokens_per_s"], unit="tokens/s", cores=int(all_threads), kind="oracle", sample=sample,
+                seconds_per_step=multi["seconds_per_step"], cpu_model=cpu_model(), host_cpus=os.cpu_count(),
+                all_threads=multi, single_thread=single, workload=w.name)
+
+
+def kernel_rooflines(w, work, t_a, t_plan, t_b, t_c, t_d, traffic_for):
+    """Per-kernel figures of one workload: algorithmic bytes or flops per launch over the event-timed
+    launch duration, against the published peak that bounds the kernel."""
+    L = w.n_layers
+    def hbm(name, kernel, ms, nbytes, launches):
+        ach = nbytes / ms / 1e6
+        t = traffic_for(name)
+        return dict(kernel=kernel, bound="hbm", ms=ms, launches_per_step=launches, algorithmic_bytes=nbytes,
+                    achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS, GBps=ach,
+                    traffic=None if t is None else t["read_bytes"] + t["write_bytes"])
+    out = {
+        "cs_score_compact": hbm("cs_score_compact", "score_compact_kernel (+ clear_words_kernel)", t_a, work["a_bytes"], 1),
+        "cs_plan_refresh": dict(kernel="plan_frames_kernel + plan_streams_kernel + plan_fill_kernel", bound="latency",
+                                ms=t_plan, launches_per_step=1),
+        "cs_kv_rerotate": hbm("cs_kv_rerotate", "rerotate_kernel", t_b, work["b_bytes"], 1),
+        "cs_kv_refresh_scatter": hbm("cs_kv_refresh_scatter", "scatter_kernel", t_c, work["c_bytes"], L),
+    }
+    ach = work["d_flops"] / t_d / 1e9
+    t = traffic_for("cs_window_prefill_attn")
+    tm = traffic_for("attn_merge")
+    traffic = None if t is None else t["read_bytes"] + t["write_bytes"] + (0 if tm is None else tm["read_bytes"] + tm["write_bytes"])
+    name = ("window_attn_bf16_stream_kernel (+ window_attn_merge_kernel where the key sweep is split; the planning "
+            "kernel runs once per step)" if w.dtype == "bf16" and w.head_dim == 128 else
+            "window_attn_bf16_kernel" if w.dtype == "bf16" else "window_attn_f32_kernel")
+    out["cs_window_prefill_attn"] = dict(kernel=name, bound="mfma", ms=t_d, launches_per_step=L,
+                                         flops_per_launch=work["d_flops"], algorithmic_bytes=work["d_bytes"],
+                                         achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s",
+                                         frac=ach / PEAK_MFMA_BF16_TFLOPS, TFLOPs=ach,
+                                         GBps=work["d_bytes"] / t_d / 1e6, traffic=traffic)
+    return out
+
+
+def measure_workload(w, args, torch, binding, engine, keep_for_cpu):
+    """One workload: the device-planned step in a HIP graph (the figure that counts), the
+    host-planned step beside it, event-timed launches of every call, and their rooflines."""
+    import numpy as np
+    t_setup = time.perf_counter()
+    data = engine.assemble_step(w, engine.hip_scorer, device="cuda")
+    info = data.info
+    cap = lambda n: (n + n // 8 + 255) // 256 * 256
+    step = engine.DevicePlannedStep(data, reuse_cap=cap(info["n_reuse"]), q_cap=cap(info["n_q"]))
+    cpu_inputs = None
+    if keep_for_cpu:                       # a sample of the pre-step cache rows for the oracle's re-rotation leg
+        rows = int(data.plan.src_slot.shape[0])
+        pick = np.arange(rows) if rows <= 4096 else np.sort(np.random.default_rng(0).choice(rows, 4096, replace=False))
+        idx = torch.from_numpy(data.plan.src_slot[pick].astype(np.int64)).to(step.dev)
+        cpu_inputs = (step.k_pool[:, idx].cpu(), pick)
+    print(f"[bench] {w.name}: {info} setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
+
+    launch = "eager" if args.eager else "hipgraph"
+    if args.eager:
+        for _ in range(args.warmup):
+            step.run()
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
-        oc.scatter(k_l, kn, p.q_slot)
-        oc.scatter(v_l, vn, p.q_slot)
-        t_c = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        oc.window_attn(q_l, k_l, v_l, p.cu_q, p.q_pos, p.layout.block_table, w.n_q_heads,
-                       data.softmax_scale, rows=qrows)
-        t_d = (time.perf_counter() - t0) * (1.0 if qrows is None else n_q / qrows.size)
-        t_cd += t_c + t_d
-    t_step = t_a + t_b + w.n_layers * t_cd / n_l
-    sample = (f"oracle: scoring of the step's frames; re-rotation of {pick.size} of {rows} reused rows x "
-              f"{w.n_layers} layers (scaled to all rows); refresh write + attention of {n_l} of {w.n_layers} "
-              f"layers" + ("" if qrows is None else f" on {qrows.size} of {n_q} queries") + " (scaled to the full step)")
-    return dict(value=n_q / t_step, unit="tokens/s", cores=int(cores), kind="oracle", sample=sample,
-                seconds_per_step=t_step)
+        for _ in range(args.steps):
+            step.run()
+        torch.cuda.synchronize()
+        ms_per_step = 1e3 * (time.perf_counter() - t0) / args.steps
+    else:
+        ms_per_step, _graph = graph_time(torch, step.run, args.steps, args.warmup)
+    totals = step.totals.cpu().tolist()
+    if totals != [info["n_reuse"], info["n_q"], 0, 0]:
+        raise RuntimeError(f"device plan totals {totals} differ from the generator's {info['n_reuse']}, {info['n_q']}")
+    status = step.scoring_status()
+    if status != 0:
+        raise RuntimeError(f"cs_score_compact: look-back wait timed out (status word {status})")
+    # visible (query, key) pairs of the step, from the plan the GPU made
+    info["visible_pairs"] = float((step.q_pos[: info["n_q"]].to(torch.int64) + 1).sum().item())
+    work = kernel_bytes_flops(w, info, w.n_layers)
+
+    # ---- per-kernel clocks: HIP events on the launch stream around back-to-back launches
+    L = w.n_layers
+    reps = max(3, min(args.steps, 20))
+    t_a = event_time(torch, step.score_compact, reps)
+    t_plan = event_time(torch, step.plan_refresh, reps)
+    t_b = event_time(torch, step.rerotate, reps)
+    t_c = event_time(torch, lambda: [step.refresh_scatter(l) for l in range(L)], reps) / L
+    t_d = event_time(torch, lambda: [step.attention(l, reuse_plan=l > 0) for l in range(L)], reps) / L
+
+    # HBM bytes per launch from committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
+    # command (profiles/), calibrated against a plain copy: not measured live; stamped with the
+    # commit the counters were taken at; null where no such run exists for the workload
+    per_wl, traffic_commit = {}, None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            doc = json.load(open(tpath))
+            per_wl = doc.get(w.name, {})
+            traffic_commit = doc.get("_commit")
+        except Exception:
+            per_wl = {}
+    kernels = kernel_rooflines(w, work, t_a, t_plan, t_b, t_c, t_d, lambda name: per_wl.get(name))
+    share = {k: v["ms"] * v["launches_per_step"] for k, v in kernels.items()}
+    dominant = max(share, key=share.get)
+    roofline = dict(kernels[dominant])
+    roofline["call"] = dominant
+    roofline["ms_per_launch"] = roofline.pop("ms")
+    roofline["traffic_source"] = (None if roofline.get("traffic") is None else
+                                  f"profiles/pmc_traffic.json (rocprofv3 --pmc, taken at commit {traffic_commit})")
+    res = dict(workload=w.name, ms_per_step=ms_per_step, tokens_per_s=info["n_q"] / (ms_per_step * 1e-3),
+               window_tokens_per_s=info["kv_len_total"] / (ms_per_step * 1e-3), launch=launch, dtype=w.dtype,
+               streams=w.n_streams, layers=L, heads=f"{w.n_q_heads}/{w.n_kv_heads}", head_dim=w.head_dim,
+               window_frames=w.window, stride_frames=w.stride, tokens_per_frame=w.tokens_per_frame,
+               executed_tokens=info["n_q"], reused_rows=info["n_reuse"], window_tokens=info["kv_len_total"],
+               reuse_cap=step.reuse_cap, q_cap=step.q_cap, kernels=kernels, roofline=roofline,
+               kernel_ms_sum=sum(share.values()))
+    if not args.no_host_plan:
+        hstep = engine.DeviceStep(data, host_plan=True)
+        if args.eager:
+            hstep.run(); torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                hstep.run()
+            torch.cuda.synchronize()
+            res["host_planned_ms_per_step"] = 1e3 * (time.perf_counter() - t0) / args.steps
+        else:
+            res["host_planned_ms_per_step"], _g2 = graph_time(torch, hstep.run, args.steps, args.warmup)
+            del _g2
+        res["host_route_ms"] = host_route_time(w, data, step, torch)
+        del hstep
+    return res, data, step, cpu_inputs, work
 
 
 def main():
@@ -364,7 +489,6 @@ def main():
         print("bench.py: this build runs on ONE GPU only (the path shards by stream with no exchange step; "
               "no multi-GPU figure is produced). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
-    import numpy as np
     import torch
     from paper_2604_06036_amd import binding, engine, synth
 
@@ -376,129 +500,61 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
-    w = synth.WORKLOADS[args.workload]
-    t_setup = time.perf_counter()
-    data = engine.assemble_step(w, engine.hip_scorer, device="cuda")
-    step = engine.DeviceStep(data)
-    step.k_pool_before = step.k_pool.clone()     # pre-step cache, for the CPU baseline's re-rotation leg
-    info = data.info
-    work = kernel_bytes_flops(w, info, w.n_layers)
-    print(f"[bench] {w.name}: {info} setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
+    names = [args.workload] if args.workload else list(DEFAULT_WORKLOADS)
+    headline = names[-1]
+    side_name = args.side_legs_workload if (len(names) > 1 and args.side_legs_workload in names) else headline
+    results, side, cpu = [], {}, None
+    for name in names:
+        w = synth.WORKLOADS[name]
+        res, data, step, cpu_inputs, work = measure_workload(w, args, torch, binding, engine,
+                                                             keep_for_cpu=(name == headline and not args.no_cpu_baseline))
+        results.append(res)
+        reps = max(3, min(args.steps, 20))
+        if name == side_name:
+            if not args.no_scaled_scoring:
+                side["score_compact_scaled"] = scaled_scoring(w, torch, binding)
+                side["block_projection"] = block_projection(w, torch, binding, reps)
+                side["residual_proxy"] = residual_proxy(w, torch, binding, reps)
+                side["kv_rerotate_axes"] = axes_rerotation(w, step, torch, binding, work["b_bytes"], reps)
+            if not args.no_frontend_step:
+                side["frontend_step"] = frontend_step(w, torch, engine, args.steps, args.warmup)
+            side["side_legs_workload"] = name
+        if cpu_inputs is not None:
+            cpu = cpu_baseline(w, data, step, cpu_inputs[0], cpu_inputs[1], torch)
+        del data, step, cpu_inputs
+        torch.cuda.empty_cache()
 
-    # ---- the timed region: W warm-up steps, then exactly K steps
-    launch = "eager"
-    run_step = step.run
-    graph = None
-    if not args.eager:
-        try:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                step.run()
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                step.run()
-            run_step = graph.replay
-            launch = "hipgraph"
-        except Exception as exc:  # capture unsupported: fall back to eager launches, and say so
-            print(f"[bench] graph capture failed ({exc}); using eager launches", file=sys.stderr)
-            run_step, launch = step.run, "eager"
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
-    tokens_per_s = info["n_q"] / (ms_per_step * 1e-3)
-
-    # ---- per-kernel clocks: HIP events on the launch stream around back-to-back launches
-    L = w.n_layers
-    reps = max(3, min(args.steps, 20))
-    t_a = event_time(torch, step.score_compact, reps)
-    t_b = event_time(torch, step.rerotate, reps)
-    t_c = event_time(torch, lambda: [step.refresh_scatter(l) for l in range(L)], reps) / L
-    t_d = event_time(torch, lambda: [step.attention(l, reuse_plan=l > 0) for l in range(L)], reps) / L
-    kernels = {
-        "cs_score_compact": dict(ms=t_a, launches_per_step=1, GBps=work["a_bytes"] / t_a / 1e6),
-        "cs_kv_rerotate": dict(ms=t_b, launches_per_step=1, GBps=work["b_bytes"] / t_b / 1e6),
-        "cs_kv_refresh_scatter": dict(ms=t_c, launches_per_step=L, GBps=work["c_bytes"] / t_c / 1e6),
-        "cs_window_prefill_attn": dict(ms=t_d, launches_per_step=L, TFLOPs=work["d_flops"] / t_d / 1e9,
-                                       GBps=work["d_bytes"] / t_d / 1e6),
-    }
-    share = {k: v["ms"] * v["launches_per_step"] for k, v in kernels.items()}
-    dominant = max(share, key=share.get)
-    # HBM bytes per launch of the dominant kernel, from committed rocprofv3 --pmc FETCH_SIZE /
-    # WRITE_SIZE runs of this same command, calibrated against a 1 GiB copy (profiles/): not
-    # measured live, null when no such run exists for this workload
-    traffic, traffic_detail = None, None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            per_wl = json.load(open(tpath)).get(w.name, {})
-            traffic_detail = per_wl.get(dominant)
-            if traffic_detail:
-                traffic = traffic_detail["read_bytes"] + traffic_detail["write_bytes"]
-                merge = per_wl.get("attn_merge") if dominant == "cs_window_prefill_attn" else None
-                if merge:                                    # split sweeps: the call is two kernels
-                    traffic += merge["read_bytes"] + merge["write_bytes"]
-                    traffic_detail = dict(traffic_detail, merge_kernel=merge)
-        except Exception:
-            traffic, traffic_detail = None, None
-    if dominant == "cs_window_prefill_attn":
-        ach = kernels[dominant]["TFLOPs"]
-        roofline = dict(bound="mfma", kernel=("window_attn_bf16_stream_kernel (+ window_attn_merge_kernel where the key sweep is split)"
-                                if w.dtype == "bf16" and w.head_dim == 128 else
-                                "window_attn_bf16_kernel" if w.dtype == "bf16" else "window_attn_f32_kernel"),
-                        achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS,
-                        traffic=traffic, traffic_detail=traffic_detail, algorithmic_bytes=work["d_bytes"],
-                        flops_per_launch=work["d_flops"], ms_per_launch=t_d)
-    else:
-        ach = kernels[dominant]["GBps"]
-        key = {"cs_score_compact": "a_bytes", "cs_kv_rerotate": "b_bytes", "cs_kv_refresh_scatter": "c_bytes"}[dominant]
-        roofline = dict(bound="hbm", kernel=dominant, achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=ach / PEAK_HBM_GBS, traffic=traffic, traffic_detail=traffic_detail, bytes_per_launch=work[key],
-                        ms_per_launch=kernels[dominant]["ms"])
-
+    head = results[-1]
     out = {
-        "metric": "window-prefill tokens/s per MI355X (executed refresh+new+text tokens per second, whole step)",
-        "value": tokens_per_s,
+        "metric": "window-prefill tokens/s per MI355X (executed refresh+new+text tokens per second, whole step "
+                  "with the refresh plan made on the GPU)",
+        "value": head["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": w.dtype,
+        "dtype": head["dtype"],
         "data": "synthetic",
-        "config": {"workload": w.name, "streams": w.n_streams, "layers": w.n_layers,
-                   "heads": f"{w.n_q_heads}/{w.n_kv_heads}", "head_dim": w.head_dim,
-                   "window_frames": w.window, "stride_frames": w.stride, "tokens_per_frame": w.tokens_per_frame,
-                   "executed_tokens": info["n_q"], "reused_rows": info["n_reuse"],
-                   "window_tokens": info["kv_len_total"], "launch": launch},
-        "window_tokens_per_s": info["kv_len_total"] / (ms_per_step * 1e-3),
-        "kernels": kernels,
-        "roofline": roofline,
+        "config": {"workload": head["workload"], "streams": head["streams"], "layers": head["layers"],
+                   "heads": head["heads"], "head_dim": head["head_dim"], "window_frames": head["window_frames"],
+                   "stride_frames": head["stride_frames"], "tokens_per_frame": head["tokens_per_frame"],
+                   "executed_tokens": head["executed_tokens"], "reused_rows": head["reused_rows"],
+                   "window_tokens": head["window_tokens"], "launch": head["launch"],
+                   "plan": "device (cs_plan_refresh inside the step)"},
+        "window_tokens_per_s": head["window_tokens_per_s"],
+        "kernels": head["kernels"],
+        "roofline": head["roofline"],
+        "workloads": results,
     }
     if args.calibrate_copy:
         out["copy_calibration"] = copy_calibration(torch)
-    if not args.no_scaled_scoring:
-        out["score_compact_scaled"] = scaled_scoring(w, torch, binding)
-        out["block_projection"] = block_projection(w, torch, binding, reps)
-        out["residual_proxy"] = residual_proxy(w, torch, binding, reps)
-        out["kv_rerotate_axes"] = axes_rerotation(w, step, torch, binding, work["b_bytes"], reps)
-    if not args.no_frontend_step:
-        out["frontend_step"] = frontend_step(w, torch, engine, args.steps, args.warmup)
-    if not args.no_device_plan:
-        out["device_planned_step"] = device_planned(w, data, torch, engine, args.steps, args.warmup)
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, data, step, torch)
+    out.update(side)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

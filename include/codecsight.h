@@ -172,13 +172,22 @@ int cs_residual_proxy(const uint8_t* cur, const uint8_t* prev, const int16_t* mv
  *                                            strictly ascending; the tail is left untouched
  *  kept_off   out  int32  [n_frames+1]       exclusive prefix of per-frame kept counts
  *  workspace       cs_score_compact_workspace() bytes, 8-byte aligned; contents need not be
- *                  initialised and are meaningless afterwards.  Two calls that overlap in time
- *                  must not share a workspace.
+ *                  initialised.  Two calls that overlap in time must not share a workspace.
+ *                  After the call has completed on the stream, the 32-bit word at byte offset
+ *                  CS_SCORE_STATUS_OFFSET of the workspace is the call's device status: 0, or 1
+ *                  when a tile's wait for the kept-token count of its predecessors ran out (the
+ *                  wait is bounded so that every wave exits; it expires only if a workgroup of the
+ *                  launch never ran).  With status 1 kept_idx / kept_off are not valid.  The rest
+ *                  of the workspace is meaningless afterwards.  The return value cannot carry this
+ *                  (the call never synchronises): callers that must know read the word after
+ *                  synchronising.
  * Errors: CS_EINVAL (null required pointer, n_streams < 0, n_frames < 0, grid < 1,
  *         grid not divisible by group, sad/use_residual mismatch), CS_EUNSUPPORTED (group not in
  *         {1,2}, n_frames*T >= 2^31), CS_EWORKSPACE, CS_EHIP.  n_streams == 0 or n_frames == 0
  *         writes kept_off[0..n_frames] = 0 and returns CS_OK.
  * ------------------------------------------------------------------------------------------ */
+#define CS_SCORE_STATUS_OFFSET 4   /* byte offset of the device status word in the workspace */
+
 size_t cs_score_compact_workspace(int32_t n_streams, int32_t n_frames,
                                   int32_t grid_h, int32_t grid_w, int32_t group);
 
@@ -344,8 +353,11 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  *  cu_q          int32 [n_streams+1], cu_q[0] = 0, cu_q[n_streams] <= n_q: n_q sizes the launch
  *                and may be an upper bound (rows from cu_q[n_streams] on are neither read nor
  *                written), so that a plan made on the device needs no host copy of its totals
- *  q_pos         int32 [n_q];  kv_len int32 [n_streams]: q_pos < kv_len, and block_table row s
- *                defines entries 0 .. ceil(kv_len[s]/16)-1
+ *  q_pos         int32 [n_q], non-negative, non-decreasing inside a stream;  kv_len int32
+ *                [n_streams]: block_table row s defines entries 0 .. ceil(kv_len[s]/16)-1.  A
+ *                q_pos at or past kv_len[s] (or past max_blocks*16) is read as the last defined
+ *                entry, so the call never indexes beyond the rows the table defines; the rows of
+ *                a stream with kv_len <= 0 are not computed (their `out` rows stay untouched)
  *  block_table   int32 [n_streams][max_blocks]
  *  workspace     cs_window_prefill_attn_workspace() bytes for the same shape arguments, 16-byte
  *                aligned (may be 0, then NULL is accepted).  Holds the work plan of the launch
@@ -362,7 +374,7 @@ int cs_kv_refresh_scatter(const void* k_new, const void* v_new, const int32_t* s
  *                prefer every layer to run in REUSE mode.  Ignored where no plan is used (CS_F32, head_dim 64: an
  *                ONLY call then computes like any other).
  * Errors: CS_EINVAL (null pointer, negative size, n_q_heads not a multiple of n_kv_heads, unknown
- *         plan_mode), CS_EUNSUPPORTED (head_dim not in {64,128}, block_size != 16,
+ *         plan_mode, softmax_scale not a positive finite number), CS_EUNSUPPORTED (head_dim not in {64,128}, block_size != 16,
  *         n_q_heads/n_kv_heads > 16, strides not multiples of 16 bytes, unknown dtype; CS_BF16:
  *         n_kv_heads > 256, n_streams >= 2^23, stride_slot >= 2^26 elements or max_blocks >= 2^17
  *         with head_dim 128, max_blocks > 8192 with head_dim 64),

@@ -88,3 +88,26 @@ def plan_stream(old_types, old_counts, new_types, new_counts, n_text, tokens_per
         seq += 1
     plan["kv_len"] = seq
     return plan
+
+
+def plan_batch(old_types, old_counts, new_types, new_counts, n_text, tokens_per_frame,
+               old_block_table, new_block_table, block=16):
+    """`plan_stream` for every stream of a batch, lists concatenated stream-major (Sec. 3.5: streams
+    are independent; their executed rows share one variable-length launch).
+
+    old_types / old_counts [B][W], new_types / new_counts [B][S], block tables [B][max_blocks].
+    Returns a dict of Python lists: src_slot, dst_slot, delta (reused rows), q_pos, q_slot, q_kind
+    (executed rows), cu_q [B+1] (first executed row of each stream) and kv_len [B].
+    """
+    keys = ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "q_kind")
+    out = {k: [] for k in keys}
+    out["cu_q"] = [0]
+    out["kv_len"] = []
+    for s in range(len(old_types)):
+        one = plan_stream(list(old_types[s]), list(old_counts[s]), list(new_types[s]), list(new_counts[s]),
+                          n_text, tokens_per_frame, old_block_table[s], new_block_table[s], block)
+        for k in keys:
+            out[k] += one[k]
+        out["cu_q"].append(len(out["q_pos"]))
+        out["kv_len"].append(one["kv_len"])
+    return out

@@ -147,6 +147,18 @@ def cs_score_compact(mv, sad, intra, frame_type, cu_frames, acc_mask, n_streams,
         _ptr(keep_mask), _ptr(kept_idx), _ptr(kept_off), _ptr(workspace), workspace_bytes, _stream()))
 
 
+CS_SCORE_STATUS_OFFSET = 4
+
+
+def cs_score_compact_status(workspace, workspace_bytes=None) -> int:
+    """The device status word cs_score_compact leaves in its workspace (0 = good).  The caller
+    synchronises first; this only copies the word back."""
+    if workspace is None or workspace.numel() * workspace.element_size() < CS_SCORE_STATUS_OFFSET + 4:
+        return 0
+    flat = workspace.view(-1).view(__import__("torch").uint8)
+    return int(flat[CS_SCORE_STATUS_OFFSET:CS_SCORE_STATUS_OFFSET + 4].view(__import__("torch").int32).item())
+
+
 def cs_kv_rerotate(k_cache, v_cache, src_slot, dst_slot, delta, n_rows, n_layers, n_kv_heads, head_dim,
                    stride_layer, stride_slot, stride_head, rope_base, rope_style, dtype):
     for t, what in ((src_slot, "src_slot"), (dst_slot, "dst_slot"), (delta, "delta")):

@@ -332,7 +332,11 @@ __device__ uint32_t look_back(const ScoreParams& p, uint32_t tile, uint32_t aggr
       if (idx >= 0)
         st = __hip_atomic_load(&p.tile_state[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       ready = __all(st != 0);
-      if (!ready && ++polls > kSpinLimit) {               // never taken in a correct run
+      // give up after kSpinLimit polls, or as soon as another tile has given up (a stalled
+      // predecessor would otherwise make every later tile spin its full limit in turn)
+      if (!ready && (++polls > kSpinLimit ||
+                     ((polls & 1023u) == 0 &&
+                      __hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0))) {   // never taken in a correct run
         if (lane == 0) __hip_atomic_store(p.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (st == 0) st = kFlagPrefix;
         ready = true;

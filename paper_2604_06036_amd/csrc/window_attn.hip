@@ -29,6 +29,17 @@
 
 #include "common.h"
 
+#ifndef CS_X_SWAP
+#define CS_X_SWAP 1
+#endif
+#ifndef CS_X_ADDR
+#define CS_X_ADDR 1
+#endif
+#ifndef CS_X_WNUM
+#define CS_X_WNUM 4
+#define CS_X_WDEN 3
+#endif
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -120,15 +131,18 @@ __global__ __launch_bounds__(256, 2) void window_attn_bf16_kernel(AttnParams p) 
   const int row_c = valid ? row : rows_total - 1;
   const int tok = q0 + row_c / p.group;
   const int head = kvh * p.group + row_c % p.group;
-  const int lim = valid ? p.q_pos[tok] : -1;
+  // a frontier never lies past the entries the stream's block-table row defines
+  const int cap = min(p.kv_len[s], p.max_blocks * CS_KV_BLOCK) - 1;
+  const int lim = valid ? min(p.q_pos[tok], cap) : -1;
 
   const int wg_last = min(r_tile + kBM, rows_total) - 1;
-  const int wg_max = p.q_pos[q0 + wg_last / p.group];
+  const int wg_max = min(p.q_pos[q0 + wg_last / p.group], cap);
   const int w_first = r_tile + wave * 32;
   const bool wave_live = w_first < rows_total;
   const int w_last = min(w_first + 31, rows_total - 1);
-  const int wave_min = wave_live ? p.q_pos[q0 + w_first / p.group] : -1;
-  const int wave_max = wave_live ? p.q_pos[q0 + w_last / p.group] : -1;
+  const int wave_min = wave_live ? min(p.q_pos[q0 + w_first / p.group], cap) : -1;
+  const int wave_max = wave_live ? min(p.q_pos[q0 + w_last / p.group], cap) : -1;
+  if (wg_max < 0) return;                 // the stream defines no cache entry: nothing to attend to
   const int n_key_tiles = wg_max / kBN + 1;
   const int last_blk = wg_max / CS_KV_BLOCK;
 
@@ -400,6 +414,7 @@ struct PlanParams {
   const int32_t* __restrict__ cu_q;
   const int32_t* __restrict__ q_pos;
   const int32_t* __restrict__ block_table;
+  const int32_t* __restrict__ kv_len;
   int32_t max_blocks;
   int32_t n_streams, group, n_kv_heads, chunk_tiles, max_splits, max_tiles, r_cap, bm, n_slots, hist_pitch;   // n_slots: workgroups per XCD
   int32_t* header;      // [kPlanHeaderInts]
@@ -435,6 +450,12 @@ __device__ __forceinline__ int plan_block_scan(int v, int* s_wave, int& total) {
   return base + incl - v;
 }
 
+// Rows (query tokens x query heads of one kv group) of a stream; a stream whose block-table row
+// defines no entry (kv_len <= 0) has nothing to attend to and gets no row tiles.
+__device__ __forceinline__ int plan_stream_rows(const PlanParams& pp, int s) {
+  return pp.kv_len[s] > 0 ? (pp.cu_q[s + 1] - pp.cu_q[s]) * pp.group : 0;
+}
+
 __device__ __forceinline__ int plan_xcd_of_pair(int pair) {
   const int round = pair >> 3, pos = pair & 7;
   return (round & 1) ? 7 - pos : pos;
@@ -455,7 +476,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     const int s = s0 + tid;
     int tiles = 0;
     if (s < pp.n_streams) {
-      const int rows = (pp.cu_q[s + 1] - pp.cu_q[s]) * pp.group;
+      const int rows = plan_stream_rows(pp, s);
       tiles = (rows + pp.bm - 1) / pp.bm;
       pp.st_work[s] = 0;
     }
@@ -479,12 +500,13 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     const int s = lo;
     const int t = r - pp.st_toff[s];
     const int q0 = pp.cu_q[s];
-    const int rows = (pp.cu_q[s + 1] - q0) * pp.group;
+    const int rows = plan_stream_rows(pp, s);
     const int last_row = min((t + 1) * pp.bm, rows) - 1;
-    const int wg_max = pp.q_pos[q0 + last_row / pp.group];
+    // the tile's frontier, kept inside the entries the stream's block-table row defines
+    const int wg_max = max(0, min(pp.q_pos[q0 + last_row / pp.group], min(pp.kv_len[s], pp.max_blocks * CS_KV_BLOCK) - 1));
     pp.rt_stream[r] = s;
     pp.rt_wgmax[r] = wg_max;
-    atomicAdd(&pp.st_work[s], wg_max / kBN + 1);
+    atomicAdd(&pp.st_work[s], max(wg_max, 0) / kBN + 1);
   }
   __threadfence_block();
   __syncthreads();
@@ -536,7 +558,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   };
   for (int r = tid; r < n_rt; r += kPlanThreads) {
     const int s = pp.rt_stream[r];
-    const int n_kt = pp.rt_wgmax[r] / kBN + 1;
+    const int n_kt = max(pp.rt_wgmax[r], 0) / kBN + 1;
     const int n_split = pp.max_splits > 1 ? min((n_kt + pp.chunk_tiles - 1) / pp.chunk_tiles, pp.max_splits) : 1;
     for (int kvh = 0; kvh < pp.n_kv_heads; ++kvh)
       for (int c = 0; c < n_split; ++c) {
@@ -592,10 +614,10 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     const int s = pp.rt_stream[r];
     const int t = r - pp.st_toff[s];
     const int q0 = pp.cu_q[s];
-    const int rows = (pp.cu_q[s + 1] - q0) * pp.group;
+    const int rows = plan_stream_rows(pp, s);
     const int tiles_s = (rows + pp.bm - 1) / pp.bm;
     const int wg_max = pp.rt_wgmax[r];
-    const int n_kt = wg_max / kBN + 1;
+    const int n_kt = max(wg_max, 0) / kBN + 1;
     const int n_split = pp.max_splits > 1 ? min((n_kt + pp.chunk_tiles - 1) / pp.chunk_tiles, pp.max_splits) : 1;
     for (int kvh = 0; kvh < pp.n_kv_heads; ++kvh) {
       const int rt_id = r * pp.n_kv_heads + kvh;
@@ -668,7 +690,11 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
           if (taken == 2) first3[2] = idx;
           ++taken;
           last = idx;
+#ifdef CS_X_WNUM
+          load += (2 * (got >> 8) + kItemFixedCostHalves) * (lane >= 32 ? CS_X_WNUM : CS_X_WDEN);
+#else
           load += 2 * (got >> 8) + kItemFixedCostHalves;
+#endif
         }
         __builtin_amdgcn_wave_barrier();
       }
@@ -693,6 +719,13 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     }
   }
 }
+
+#if CS_X_TS
+__device__ uint32_t g_ts[512 * 4 * 8];
+typedef __attribute__((ext_vector_type(2))) uint32_t ts_t;
+__device__ __forceinline__ ts_t ts_now() { ts_t v; asm volatile("s_memtime %0" : "=&s"(v)); return v; }
+#define TS_ADD(acc, a, b) acc += (b)[0] - (a)[0]
+#endif
 
 // Scalar loads issued by hand: the results are uniform, travel outside the vector-memory queue
 // (so waiting for them never drains tile requests) and are only read after the explicit wait.
@@ -723,10 +756,21 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   __shared__ __attribute__((aligned(1024))) uint16_t sK[2][TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t sV[2][TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t s_sink[4][512];   // see request_part
+#if CS_X_OCC1
+  __shared__ uint16_t s_pad[24576];
+  reinterpret_cast<volatile uint16_t*>(s_pad)[threadIdx.x] = 0;
+#endif
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
+#if CS_X_PRIO == 1
+  if (__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 4) & 1) __builtin_amdgcn_s_setprio(3);
+#elif CS_X_PRIO == 2
+  if ((blockIdx.x >> 8) & 1) __builtin_amdgcn_s_setprio(3);
+#elif CS_X_PRIO == 3
+  if ((blockIdx.x >> 3) & 1) __builtin_amdgcn_s_setprio(3);
+#endif
 
   // ---- this workgroup's items: a chain through the `next` field of the descriptors, dealt by the
   //      planning kernel; three descriptors of look-ahead are kept loaded
@@ -766,6 +810,14 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
 #pragma unroll
   for (int db = 0; db < DB; ++db)
     v_rd[db] = v_row * D + (((4 * db + 2 * gid + ((i16 & 3) >> 1)) ^ v_swz) << 3) + 4 * (i16 & 1);
+
+#if CS_X_ADDR
+  uint32_t k_addr[STEPS], v_addr[DB];   // LDS byte addresses of this lane's fragments in stage 0
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st) k_addr[st] = lds_address(&sK[0][0]) + 2 * k_rd[st];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) v_addr[db] = lds_address(&sV[0][0]) + 2 * v_rd[db];
+#endif
 
   // ---- a slot of the tile stream: one key tile of one item, with the cache-block ids its
   //      request needs (this wave's quarter of the tile, and the block of the item's frontier)
@@ -888,7 +940,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
 #pragma unroll
       for (int st = 0; st < STEPS; ++st)
         qf[rb][st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(qrow + 16 * st + 8 * h));
-      lim_raw[rb] = p.q_pos[tok];
+      lim_raw[rb] = min(p.q_pos[tok], d[4]);      // d[4]: the tile's frontier, already inside the stream's entries
     }
   };
 
@@ -914,11 +966,36 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
     const uint16_t* tV = sV[stage];
     f32x16 sacc[RB][2];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    constexpr int KPF = 2;               // K fragments are read two steps ahead of their MFMAs
+#ifndef CS_X_KPF
+#define CS_X_KPF 2
+#endif
+#ifndef CS_X_VPF
+#define CS_X_VPF 3
+#endif
+    constexpr int KPF = CS_X_KPF;        // K fragments are read two steps ahead of their MFMAs
     bf16x8 ka[KPF + 1][2];
+#if CS_X_ADDR
+    typedef __attribute__((address_space(3))) const cs::u32x4 lds_u32x4;
+    const uint32_t stage_off = static_cast<uint32_t>(stage) * (TILE * 2);
+    uint32_t kad[STEPS], va[DB];
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+      kad[st] = k_addr[st] + stage_off;
+      asm volatile("" : "+v"(kad[st]));
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      va[db] = v_addr[db] + stage_off;
+      asm volatile("" : "+v"(va[db]));
+    }
+    auto k_frag = [&](int st, int kb) {
+      return __builtin_bit_cast(bf16x8, reinterpret_cast<lds_u32x4*>(static_cast<uintptr_t>(kad[st]))[kb * 32 * D * 2 / 16]);
+    };
+#else
     auto k_frag = [&](int st, int kb) {
       return __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(&tK[kb * 32 * D + k_rd[st]]));
     };
+#endif
 #pragma unroll
     for (int st = 0; st < KPF; ++st) {
       ka[st][0] = k_frag(st, 0);
@@ -963,17 +1040,31 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[rb][kb][r]);
+#if CS_X_SWAP
+      {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(t_max), __float_as_uint(t_max), false, false);
+        t_max = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+      }
+#else
       t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
+#endif
       if (__any(t_max > m_run[rb] + slack)) {
         const bool up = t_max > m_run[rb] + slack;
         const float m_new = up ? t_max : m_run[rb];
         const float alpha = up ? __builtin_amdgcn_exp2f((m_run[rb] - m_new) * p.scale_log2e) : 1.f;
+#if CS_X_NORESCALE0
+        const bool fresh = __all(m_run[rb] == kNegInf);
+#else
+        const bool fresh = false;
+#endif
         m_run[rb] = m_new;
         l_run[rb] *= alpha;
+        if (!fresh) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+          for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) o[rb][db][r] *= alpha;
+            for (int r = 0; r < 16; ++r) o[rb][db][r] *= alpha;
+        }
       }
       const float m_scaled = (m_run[rb] == kNegInf ? 0.f : m_run[rb]) * p.scale_log2e;
 #pragma unroll
@@ -983,8 +1074,13 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
           cs::u32x4 w;
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
+#if CS_X_NOEXP
+            const float e0 = sacc[rb][kb][8 * mm + 2 * c] - m_scaled;
+            const float e1 = sacc[rb][kb][8 * mm + 2 * c + 1] - m_scaled;
+#else
             const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[rb][kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
             const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[rb][kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
+#endif
             const uint32_t pk = pack_bf16x2(e0, e1);
             l_run[rb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
                                                         __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run[rb], false);
@@ -994,13 +1090,22 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
         }
     }
     // 16 MFMAs, m = (key block, key half, d block); V^T fragments are read VPF MFMAs ahead
-    constexpr int VPF = 3;
+    constexpr int VPF = CS_X_VPF;
     s16x4 vlo[VPF + 1], vhi[VPF + 1];
+#if CS_X_ADDR
+    auto v_frag = [&](int m) {
+      const int g0 = (32 * (m >> 3) + 16 * ((m >> 2) & 1)) * D, db = m & 3;
+      const uint32_t a = va[db];
+      vlo[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(((lds_s16x4*)(static_cast<uintptr_t>(a))) + g0 * 2 / 8);
+      vhi[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(((lds_s16x4*)(static_cast<uintptr_t>(a))) + (g0 + 8 * D) * 2 / 8);
+    };
+#else
     auto v_frag = [&](int m) {
       const int g0 = (32 * (m >> 3) + 16 * ((m >> 2) & 1)) * D, db = m & 3;
       vlo[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + v_rd[db]]));
       vhi[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + 8 * D + v_rd[db]]));
     };
+#endif
 #pragma unroll
     for (int m = 0; m < VPF; ++m) v_frag(m);
 #pragma unroll
@@ -1076,7 +1181,13 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   }
   int stage = 0;
 
+#if CS_X_TS
+  uint32_t ts_vm = 0, ts_bar = 0, ts_book = 0, ts_comp = 0, ts_tail = 0, ts_ncomp = 0, ts_nskip = 0, ts_ep = 0;
+#endif
   for (;;) {
+#if CS_X_TS
+    ts_t ts0 = ts_now();
+#endif
     // everything requested so far has landed: the tile of `cur`, and at an item boundary the Q
     // rows and frontier of its item (telling the compiler so here keeps it from waiting for them
     // later, when that wait would also cover the tile request issued below)
@@ -1088,6 +1199,9 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       asm volatile("" : "+v"(lim_raw[rb]));
     }
     __syncthreads();                     // every wave's share landed; every wave left the other stage
+#if CS_X_TS
+    ts_t ts2 = ts_now();
+#endif
     if (new_item) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) lim[rb] = it_valid[rb] ? lim_raw[rb] : -1;
@@ -1120,9 +1234,20 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       finish_item(ep_tok_head, ep_valid, ep_part);
       ep_pending = false;
     }
+#if CS_X_TS
+    ts_t ts3 = ts_now();
+#endif
     if (computes) compute(cur.kt, stage);
+#if CS_X_TS
+    ts_t ts4 = ts_now();
+#endif
 
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nn.id), "+s"(nn.last_id), "+s"(d3));
+#if CS_X_TS
+    asm volatile("" : "+s"(ts0), "+s"(ts2), "+s"(ts3), "+s"(ts4));
+    TS_ADD(ts_bar, ts0, ts2); TS_ADD(ts_book, ts2, ts3); TS_ADD(ts_comp, ts3, ts4);
+    if (computes) ++ts_ncomp; else ++ts_nskip;
+#endif
     if (cur_last) {
       ep_pending = true;
 #pragma unroll
@@ -1138,12 +1263,21 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       d0 = d1; d1 = d2; d2 = d3;
       ++seq0;
     }
+#if CS_X_TS
+    { ts_t ts5 = ts_now(); asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(ts5)); TS_ADD(ts_tail, ts4, ts5); }
+#endif
     if (!nxt.live) break;
     cur = nxt;
     nxt = nn;
     stage ^= 1;
   }
   finish_item(ep_tok_head, ep_valid, ep_part);
+#if CS_X_TS
+  if (lane == 0) {
+    uint32_t* t = g_ts + (blockIdx.x * 4 + wave) * 8;
+    t[0] = ts_vm; t[1] = ts_bar; t[2] = ts_book; t[3] = ts_ep; t[4] = ts_comp; t[5] = ts_tail; t[6] = ts_ncomp; t[7] = ts_nskip;
+  }
+#endif
 }
 
 // Merges the partial results of split row tiles: out = sum_c w_c O_c / sum_c w_c l_c with
@@ -1209,7 +1343,8 @@ __global__ __launch_bounds__(256) void window_attn_f32_kernel(AttnParams p) {
   int s = 0;
   while (s + 1 < p.n_streams && p.cu_q[s + 1] <= tok) ++s;
   const int32_t* bt = p.block_table + static_cast<int64_t>(s) * p.max_blocks;
-  const int lim = p.q_pos[tok];
+  const int lim = min(p.q_pos[tok], min(p.kv_len[s], p.max_blocks * CS_KV_BLOCK) - 1);
+  if (lim < 0) return;                    // the stream defines no cache entry (or q_pos < 0): row left untouched
 
   const float* qrow = static_cast<const float*>(p.q) + (static_cast<int64_t>(tok) * p.n_q_heads + head) * D;
   float qv[D], acc[D];
@@ -1302,7 +1437,11 @@ AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_h
   }
   a.items_cap = a.rt_cap * a.max_splits;
   const int64_t per_xcd = (a.items_cap + 7) / 8;
+#if CS_X_OCC1
+  const int64_t cap = 32;
+#else
   const int64_t cap = a.rb == 2 ? 32 : 64;
+#endif
   a.grid = 8 * static_cast<int>(per_xcd < cap ? per_xcd : cap);
   size_t at = kPlanHeaderInts * sizeof(int32_t);
   auto take = [&](size_t bytes) {
@@ -1350,6 +1489,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   if (n_q < 0 || n_streams < 0 || n_q_heads < 1 || n_kv_heads < 1 || max_blocks < 0) return CS_EINVAL;
   if (stride_slot < 0 || stride_head < 0) return CS_EINVAL;
   if (n_q_heads % n_kv_heads) return CS_EINVAL;
+  if (!(softmax_scale > 0.f) || !isfinite(softmax_scale)) return CS_EINVAL;   // also rejects NaN
   if (dtype != CS_F32 && dtype != CS_BF16) return CS_EUNSUPPORTED;
   if (head_dim != 64 && head_dim != 128) return CS_EUNSUPPORTED;
   if (block_size != CS_KV_BLOCK) return CS_EUNSUPPORTED;
@@ -1410,6 +1550,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         pp.cu_q = cu_q;
         pp.q_pos = q_pos;
         pp.block_table = block_table;
+        pp.kv_len = kv_len;
         pp.max_blocks = max_blocks;
         pp.n_streams = n_streams;
         pp.group = group;
@@ -1459,3 +1600,9 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   }
   return cs::note_hip(hipGetLastError());
 }
+
+#if CS_X_TS
+extern "C" int cs_debug_ts(void* host, size_t bytes) {
+  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ts), bytes < sizeof(g_ts) ? bytes : sizeof(g_ts)));
+}
+#endif

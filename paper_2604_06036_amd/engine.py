@@ -1,10 +1,13 @@
-"""Drives one slide step of a batch of streams through the four device calls.
+"""Drives one slide step of a batch of streams through the device calls.
 
 `assemble_step` builds everything a step needs from a synthetic workload (history scoring to get
-the cached window's token layout, the step's own scoring, block tables, the refresh plan, and the
-Q/K/V tensors); `DeviceStep` holds those inputs on the GPU and issues the calls in the order the
-method prescribes: score+compact, re-rotate (all layers), then per layer refresh write followed by
-attention (paper Sec. 3.5: planning first, KV-context preparation next, joint prefill last).
+the cached window's token layout, the step's own scoring, block tables and the Q/K/V tensors);
+`DeviceStep` holds those inputs on the GPU and issues the calls in the order the method
+prescribes: score+compact, refresh plan, re-rotate (all layers), then per layer refresh write
+followed by attention (paper Sec. 3.5: planning first, KV-context preparation next, joint prefill
+last).  The refresh plan is made on the GPU (cs_plan_refresh) and nothing passes through the host
+between the calls; the NumPy planner in `planner.py` is a cross-check for tests and comparison
+runs (`DeviceStep(..., host_plan=True)`), never part of the default route.
 
 The scoring function is a parameter so that the same assembly can be driven by the HIP kernels
 (`hip_scorer`, the product path) or, in tests, by the CPU oracle; nothing here falls back to a CPU
@@ -61,9 +64,9 @@ class StepData:
     frame_type: np.ndarray
     cu_frames: np.ndarray
     acc_in: np.ndarray                 # accumulated mask carried in from the history
-    # layouts and plan
+    # layouts: the cached window, and the new window's frame types / kept counts / block table
     old_layout: planner.WindowLayout
-    plan: planner.StepPlan
+    new_layout: planner.WindowLayout
     n_slots: int
     # tensors (torch): pool [L, n_slots, Hkv, d]; q [L, n_q, Hq, d]; k_new, v_new [L, n_q, Hkv, d]
     k_pool: object = None
@@ -73,6 +76,19 @@ class StepData:
     v_new: object = None
     softmax_scale: float = 0.0
     info: dict = field(default_factory=dict)
+    _plan: object = None
+
+    @property
+    def plan(self) -> planner.StepPlan:
+        """The step's row lists as the host planner makes them (built on first use): the
+        cross-check of cs_plan_refresh in tests and the lists of a `host_plan=True` step."""
+        if self._plan is None:
+            w = self.workload
+            new = self.new_layout
+            self._plan = planner.plan_slide(self.old_layout, new.frame_type[:, w.window - w.stride:],
+                                            new.counts[:, w.window - w.stride:], new.block_table,
+                                            w.tokens_per_frame)
+        return self._plan
 
 
 def assemble_step(w: synth.Workload, scorer: Scorer, device="cpu", with_tensors: bool = True) -> StepData:
@@ -118,18 +134,20 @@ def assemble_step(w: synth.Workload, scorer: Scorer, device="cpu", with_tensors:
         at += int(nb_new[s])
     n_slots = int(ids.shape[0]) * synth.KV_BLOCK
 
-    # 4. plan
+    # 4. the two window layouts; the step's sizes follow from the counts alone (reused rows = kept
+    #    tokens of the overlap's P-frames, executed rows = overlap I-frames + new frames + text)
     old_layout = planner.WindowLayout(old_types.astype(np.uint8), old_counts, w.n_text, bt_old)
-    plan = planner.plan_slide(old_layout, new_types, new_counts, bt_new, t_per)
-
+    new_layout = planner.WindowLayout(np.concatenate([old_types[:, stride:], new_types], axis=1).astype(np.uint8),
+                                      np.concatenate([old_counts[:, stride:], new_counts], axis=1).astype(np.int32),
+                                      w.n_text, bt_new)
     data = StepData(w, meta.mv[rows_new], meta.sad[rows_new], meta.frame_type[rows_new], cu_new, acc_h,
-                    old_layout, plan, n_slots, softmax_scale=1.0 / math.sqrt(w.head_dim))
-    n_q = int(plan.q_pos.shape[0])
-    vis = float(plan.kv_len.sum())
-    pairs = float((plan.q_pos.astype(np.int64) + 1).sum())
-    data.info = dict(n_q=n_q, n_reuse=int(plan.src_slot.shape[0]), kv_len_total=int(vis),
-                     visible_pairs=pairs, n_slots=n_slots,
-                     kept_new=int(new_counts.sum()), reused_fraction=float(plan.src_slot.shape[0]) / max(1.0, vis))
+                    old_layout, new_layout, n_slots, softmax_scale=1.0 / math.sqrt(w.head_dim))
+    overlap_t, overlap_c = old_types[:, stride:], old_counts[:, stride:]
+    n_reuse = int(overlap_c[overlap_t != synth.FRAME_I].sum())
+    n_q = int(overlap_c[overlap_t == synth.FRAME_I].sum() + new_counts.sum() + n_streams * w.n_text)
+    vis = float(new_len.sum())
+    data.info = dict(n_q=n_q, n_reuse=n_reuse, kv_len_total=int(vis), n_slots=n_slots,
+                     kept_new=int(new_counts.sum()), reused_fraction=float(n_reuse) / max(1.0, vis))
     if with_tensors:
         shape_pool = (w.n_layers, n_slots, w.n_kv_heads, w.head_dim)
         data.k_pool = synth.normal_tensor(w, (1,), shape_pool, device)
@@ -141,17 +159,27 @@ def assemble_step(w: synth.Workload, scorer: Scorer, device="cpu", with_tensors:
 
 
 class DeviceStep:
-    """A step resident on the GPU; each method enqueues exactly one C-ABI call."""
+    """A step resident on the GPU; each method enqueues exactly one C-ABI call.
 
-    def __init__(self, data: StepData):
+    The row lists of (b), (c), (d) are written by cs_plan_refresh from the offsets the scoring call
+    leaves in device memory: no list, count or offset passes through the host between the calls.
+    They are sized to capacities the caller budgets (`reuse_cap`, `q_cap`; default: the step's own
+    row counts); the consumers are launched over the capacities and skip the padding.
+    `host_plan=True` uploads the NumPy planner's lists instead and `run` skips the planning call
+    (tests and comparison runs)."""
+
+    def __init__(self, data: StepData, reuse_cap: Optional[int] = None, q_cap: Optional[int] = None,
+                 host_plan: bool = False):
         import torch
         from . import binding as cs
         self.cs = cs
         self.data = data
+        self.host_plan = host_plan
         w = data.workload
         dev = torch.device("cuda")
         self.dev = dev
         to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        i32 = lambda n, fill: torch.full((max(1, n),), fill, dtype=torch.int32, device=dev)
         self.dtype = cs.CS_BF16 if w.dtype == "bf16" else cs.CS_F32
         # (a)
         self.mv = to(data.mv)
@@ -159,6 +187,7 @@ class DeviceStep:
         self.frame_type = to(data.frame_type)
         self.cu_frames = to(data.cu_frames)
         self.acc = to(data.acc_in)
+        self.acc_in = self.acc.clone()
         self.n_frames = int(data.frame_type.shape[0])
         t_per = w.tokens_per_frame
         self.keep = torch.zeros((self.n_frames, t_per), dtype=torch.uint8, device=dev)
@@ -166,28 +195,52 @@ class DeviceStep:
         self.kept_off = torch.zeros((self.n_frames + 1,), dtype=torch.int32, device=dev)
         self.ws_a_bytes = cs.cs_score_compact_workspace(w.n_streams, self.n_frames, w.grid_h, w.grid_w, w.group)
         self.ws_a = torch.zeros((max(8, self.ws_a_bytes),), dtype=torch.uint8, device=dev)
+        # row lists
+        n_reuse, n_q = int(data.info["n_reuse"]), int(data.info["n_q"])
+        self.n_rows_true, self.n_q_true = n_reuse, n_q
+        self.reuse_cap = n_reuse if reuse_cap is None else int(reuse_cap)
+        self.q_cap = n_q if q_cap is None else int(q_cap)
+        if self.q_cap < n_q or self.reuse_cap < n_reuse:
+            raise ValueError("capacities below the step's row counts")
+        old, new = data.old_layout, data.new_layout
+        self.block_table = to(new.block_table)
+        self.max_blocks = int(new.block_table.shape[1])
+        if host_plan:
+            p = data.plan
+            pad = lambda a, n, fill: np.concatenate([a, np.full((n - a.shape[0],), fill, a.dtype)])
+            self.src_slot, self.dst_slot = to(pad(p.src_slot, self.reuse_cap, -1)), to(pad(p.dst_slot, self.reuse_cap, -1))
+            self.delta = to(pad(p.delta, self.reuse_cap, 0))
+            self.q_slot, self.q_pos = to(pad(p.q_slot, self.q_cap, -1)), to(pad(p.q_pos, self.q_cap, 0))
+            self.q_kind = to(pad(p.q_kind, self.q_cap, 0xFF))
+            self.cu_q, self.kv_len = to(p.cu_q), to(p.kv_len)
+        else:
+            self.src_slot, self.dst_slot, self.delta = (i32(self.reuse_cap, -9) for _ in range(3))
+            self.q_pos, self.q_slot = i32(self.q_cap, -9), i32(self.q_cap, -9)
+            self.q_kind = torch.full((max(1, self.q_cap),), 7, dtype=torch.uint8, device=dev)
+            self.cu_q, self.kv_len = i32(w.n_streams + 1, -9), i32(w.n_streams, -9)
+        self.old_types, self.old_counts = to(old.frame_type), to(old.counts)
+        self.bt_old = to(old.block_table)
+        self.max_blocks_old = int(old.block_table.shape[1])
+        self.new_types_out = torch.zeros_like(self.old_types)
+        self.new_counts_out = torch.zeros_like(self.old_counts)
+        self.totals = i32(4, -9)
+        self.ws_p_bytes = cs.cs_plan_refresh_workspace(w.n_streams, w.window)
+        self.ws_p = torch.zeros((max(8, self.ws_p_bytes),), dtype=torch.uint8, device=dev)
         # (b)
-        p = data.plan
-        self.src_slot, self.dst_slot, self.delta = to(p.src_slot), to(p.dst_slot), to(p.delta)
         self.k_pool = data.k_pool.to(dev)
         self.v_pool = data.v_pool.to(dev)
         self.stride_layer = self.k_pool.stride(0)
         self.stride_slot = self.k_pool.stride(1)
         self.stride_head = self.k_pool.stride(2)
-        # (c), (d)
-        self.q_slot, self.q_pos = to(p.q_slot), to(p.q_pos)
-        self.cu_q, self.kv_len = to(p.cu_q), to(p.kv_len)
-        self.block_table = to(p.layout.block_table)
-        self.max_blocks = int(p.layout.block_table.shape[1])
-        self.q = data.q.to(dev)
-        self.k_new = data.k_new.to(dev)
-        self.v_new = data.v_new.to(dev)
+        # (c), (d): rows beyond the step's own counts are padding (never read: slot -1 / beyond cu_q)
+        grow = lambda t: t if self.q_cap == n_q else torch.cat(
+            [t, torch.zeros((t.shape[0], self.q_cap - n_q) + tuple(t.shape[2:]), dtype=t.dtype, device=dev)], dim=1)
+        self.q, self.k_new, self.v_new = grow(data.q.to(dev)), grow(data.k_new.to(dev)), grow(data.v_new.to(dev))
         self.out = torch.zeros_like(self.q)
-        self.n_q = int(p.q_pos.shape[0])
-        ws_d = cs.cs_window_prefill_attn_workspace(self.n_q, w.n_streams, w.n_q_heads, w.n_kv_heads,
-                                                   w.head_dim, self.max_blocks, self.dtype)
-        self.ws_d_bytes = ws_d
-        self.ws_d = torch.zeros((max(8, ws_d),), dtype=torch.uint8, device=dev)
+        self.n_q = self.q_cap
+        self.ws_d_bytes = cs.cs_window_prefill_attn_workspace(self.q_cap, w.n_streams, w.n_q_heads, w.n_kv_heads,
+                                                              w.head_dim, self.max_blocks, self.dtype)
+        self.ws_d = torch.zeros((max(8, self.ws_d_bytes),), dtype=torch.uint8, device=dev)
 
     def score_compact(self):
         w = self.data.workload
@@ -196,12 +249,30 @@ class DeviceStep:
                                  w.tau_sad, w.use_residual, self.keep, self.kept_idx, self.kept_off,
                                  self.ws_a, self.ws_a_bytes)
 
+    def scoring_status(self) -> int:
+        """Status word of the last scoring call (synchronises): 0, or non-zero when a tile's bounded
+        wait for its predecessor's count ran out and the compacted lists cannot be trusted."""
+        import torch
+        torch.cuda.synchronize()
+        return self.cs.cs_score_compact_status(self.ws_a, self.ws_a_bytes)
+
+    def plan_refresh(self):
+        w = self.data.workload
+        self.cs.cs_plan_refresh(self.old_types, self.old_counts, self.frame_type, self.kept_off, self.bt_old,
+                                self.max_blocks_old, self.block_table, self.max_blocks, w.n_streams, w.window,
+                                w.stride, w.n_text, w.tokens_per_frame, self.reuse_cap, self.q_cap,
+                                self.src_slot, self.dst_slot, self.delta, self.q_pos, self.q_slot, self.q_kind,
+                                self.cu_q, self.kv_len, self.new_types_out, self.new_counts_out, self.totals,
+                                self.ws_p, self.ws_p_bytes)
+
     def rerotate(self, in_place: bool = False):
         w = self.data.workload
+        if self.reuse_cap == 0:
+            return
         self.cs.cs_kv_rerotate(self.k_pool, None if in_place else self.v_pool, self.src_slot,
                                None if in_place else self.dst_slot, self.delta,
-                               int(self.src_slot.shape[0]), w.n_layers, w.n_kv_heads, w.head_dim,
-                               self.stride_layer, self.stride_slot, self.stride_head, w.rope_base,
+                               int(self.src_slot.shape[0]) if self.reuse_cap else 0, w.n_layers, w.n_kv_heads,
+                               w.head_dim, self.stride_layer, self.stride_slot, self.stride_head, w.rope_base,
                                self.cs.CS_ROPE_HALF_SPLIT, self.dtype)
 
     def refresh_scatter(self, layer: int):
@@ -222,82 +293,25 @@ class DeviceStep:
                                        self.ws_d if self.ws_d_bytes else None, self.ws_d_bytes,
                                        self.cs.CS_ATTN_PLAN_REUSE if reuse_plan else self.cs.CS_ATTN_PLAN_BUILD)
 
-    def run(self):
-        """One pass of the whole hot path."""
-        self.score_compact()
-        self.rerotate()
-        for layer in range(self.data.workload.n_layers):
-            self.refresh_scatter(layer)
-            self.attention(layer, reuse_plan=layer > 0)
-
-
-class DevicePlannedStep(DeviceStep):
-    """The same step with the refresh plan made on the GPU (cs_plan_refresh) from the offsets the
-    scoring call leaves in device memory: no list, count or offset passes through the host between
-    the calls.  The row lists are sized to capacities the caller budgets (`reuse_cap`, `q_cap`);
-    the consumers are launched over the capacities and skip the padding."""
-
-    def __init__(self, data: StepData, reuse_cap: Optional[int] = None, q_cap: Optional[int] = None):
-        super().__init__(data)
-        import torch
-        cs, dev, w, p = self.cs, self.dev, data.workload, data.plan
-        to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-        n_reuse, n_q = int(p.src_slot.shape[0]), int(p.q_pos.shape[0])
-        self.reuse_cap = n_reuse if reuse_cap is None else int(reuse_cap)
-        self.q_cap = n_q if q_cap is None else int(q_cap)
-        if self.q_cap < n_q or self.reuse_cap < n_reuse:
-            raise ValueError("capacities below the step's row counts")
-        old = data.old_layout
-        self.old_types, self.old_counts = to(old.frame_type), to(old.counts)
-        self.bt_old = to(old.block_table)
-        self.max_blocks_old = int(old.block_table.shape[1])
-        i32 = lambda n, fill: torch.full((max(1, n),), fill, dtype=torch.int32, device=dev)
-        # the host plan's lists are dropped: everything below is written by the device planner
-        self.src_slot, self.dst_slot, self.delta = (i32(self.reuse_cap, -9) for _ in range(3))
-        self.q_pos, self.q_slot = i32(self.q_cap, -9), i32(self.q_cap, -9)
-        self.q_kind = torch.full((max(1, self.q_cap),), 7, dtype=torch.uint8, device=dev)
-        self.cu_q, self.kv_len = i32(w.n_streams + 1, -9), i32(w.n_streams, -9)
-        self.new_types_out = torch.zeros_like(self.old_types)
-        self.new_counts_out = torch.zeros_like(self.old_counts)
-        self.totals = i32(4, -9)
-        self.ws_p_bytes = cs.cs_plan_refresh_workspace(w.n_streams, w.window)
-        self.ws_p = torch.zeros((max(8, self.ws_p_bytes),), dtype=torch.uint8, device=dev)
-        if self.q_cap != n_q:
-            grow = lambda t: torch.cat([t, torch.zeros((t.shape[0], self.q_cap - n_q) + tuple(t.shape[2:]),
-                                                       dtype=t.dtype, device=dev)], dim=1)
-            self.q, self.k_new, self.v_new = grow(self.q), grow(self.k_new), grow(self.v_new)
-            self.out = torch.zeros_like(self.q)
-            self.ws_d_bytes = cs.cs_window_prefill_attn_workspace(self.q_cap, w.n_streams, w.n_q_heads,
-                                                                  w.n_kv_heads, w.head_dim, self.max_blocks,
-                                                                  self.dtype)
-            self.ws_d = torch.zeros((max(8, self.ws_d_bytes),), dtype=torch.uint8, device=dev)
-        self.n_rows_true, self.n_q_true = n_reuse, n_q
-        self.n_q = self.q_cap
-        self.acc_in = self.acc.clone()
-
-    def plan_refresh(self):
-        w = self.data.workload
-        self.cs.cs_plan_refresh(self.old_types, self.old_counts, self.frame_type, self.kept_off, self.bt_old,
-                                self.max_blocks_old, self.block_table, self.max_blocks, w.n_streams, w.window,
-                                w.stride, w.n_text, w.tokens_per_frame, self.reuse_cap, self.q_cap,
-                                self.src_slot, self.dst_slot, self.delta, self.q_pos, self.q_slot, self.q_kind,
-                                self.cu_q, self.kv_len, self.new_types_out, self.new_counts_out, self.totals,
-                                self.ws_p, self.ws_p_bytes)
-
-    def rerotate(self, in_place: bool = False):
-        if self.reuse_cap > 0:
-            super().rerotate(in_place)
-
-    def run(self):
+    def prepare(self):
+        """Scoring and planning: everything the layer loop needs in device memory."""
         # scoring updates the accumulated mask in place; a repeated run (graph replay) starts from
         # the same mask so that every repetition plans the same step
         self.acc.copy_(self.acc_in)
         self.score_compact()
-        self.plan_refresh()
+        if not self.host_plan:
+            self.plan_refresh()
+
+    def run(self):
+        """One pass of the whole hot path."""
+        self.prepare()
         self.rerotate()
         for layer in range(self.data.workload.n_layers):
             self.refresh_scatter(layer)
             self.attention(layer, reuse_plan=layer > 0)
+
+
+DevicePlannedStep = DeviceStep     # former name of the device-planned step
 
 
 @dataclass

@@ -70,3 +70,39 @@ def check_attention(gpu: torch.Tensor, ref64: np.ndarray, dtype: str):
     else:
         assert max_abs <= 2e-2 and mean_rel <= 1e-2, (max_abs, mean_rel)
     return dict(max_abs=max_abs, mean_rel=mean_rel)
+
+
+class OraclePlan:
+    """The row lists of a step as the plan ORACLE makes them (token loops in oracle/plan_oracle.py),
+    as NumPy arrays under the names the kernels' arguments have."""
+
+    def __init__(self, data):
+        from oracle import plan_oracle as po
+        w, old, new = data.workload, data.old_layout, data.new_layout
+        first_new = w.window - w.stride
+        d = po.plan_batch(old.frame_type.tolist(), old.counts.tolist(), new.frame_type[:, first_new:].tolist(),
+                          new.counts[:, first_new:].tolist(), w.n_text, w.tokens_per_frame,
+                          old.block_table, new.block_table)
+        i32 = lambda a: np.asarray(a, dtype=np.int32)
+        self.src_slot, self.dst_slot, self.delta = i32(d["src_slot"]), i32(d["dst_slot"]), i32(d["delta"])
+        self.q_pos, self.q_slot = i32(d["q_pos"]), i32(d["q_slot"])
+        self.q_kind = np.asarray(d["q_kind"], dtype=np.uint8)
+        self.cu_q, self.kv_len = i32(d["cu_q"]), i32(d["kv_len"])
+        self.block_table = new.block_table
+
+
+def assert_device_plan(step, plan: "OraclePlan"):
+    """The lists cs_plan_refresh wrote for `step` equal the plan oracle's, entry for entry; list
+    tails up to the capacities hold the padding values."""
+    n_r, n_e = plan.src_slot.size, plan.q_pos.size
+    assert step.totals.cpu().tolist() == [n_r, n_e, 0, 0], step.totals.cpu().tolist()
+    for name in ("src_slot", "dst_slot", "delta"):
+        got = getattr(step, name).cpu().numpy()
+        assert np.array_equal(got[:n_r], getattr(plan, name)), name
+        if step.reuse_cap > n_r:
+            assert np.all(got[n_r:step.reuse_cap] == (0 if name == "delta" else -1)), name
+    for name in ("q_pos", "q_slot", "q_kind"):
+        got = getattr(step, name).cpu().numpy()
+        assert np.array_equal(got[:n_e], getattr(plan, name)), name
+    assert np.array_equal(step.cu_q.cpu().numpy(), plan.cu_q)
+    assert np.array_equal(step.kv_len.cpu().numpy(), plan.kv_len)

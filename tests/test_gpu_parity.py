@@ -554,7 +554,11 @@ def test_kv_refresh_scatter(cs, dtype, n_tok, n_heads, d, layout):
 
 # =============================================================================== (d) attention
 def _attn_case(cs, rng, dtype, n_q_heads, n_kv_heads, d, kv_lens, n_qs, shuffle=True, poison=True,
-               all_queries=False):
+               all_queries=False, scale_mult=1.0, late_outlier=0.0):
+    """`scale_mult` multiplies the softmax scale (peaked rows: the running maximum keeps rising along
+    the sweep); `late_outlier` > 0 multiplies one key row near the end of every stream by that
+    factor (a maximum that jumps late, past the first tile and past the first key range of a split
+    sweep)."""
     n_streams = len(kv_lens)
     nb = [(-(-L // 16)) for L in kv_lens]
     max_blocks = max(nb) + 1
@@ -579,7 +583,12 @@ def _attn_case(cs, rng, dtype, n_q_heads, n_kv_heads, d, kv_lens, n_qs, shuffle=
     cu = np.asarray(cu, np.int32)
     n_q = int(q_pos.size)
     q = _pool(rng, (max(1, n_q), n_q_heads, d), dtype)[:n_q]
-    scale = 1.0 / math.sqrt(d)
+    scale = scale_mult / math.sqrt(d)
+    if late_outlier > 0:
+        for s in range(n_streams):
+            j = max(0, kv_lens[s] - 1 - min(40, kv_lens[s] // 3))
+            slot = int(bt[s, j // 16]) * 16 + j % 16
+            kc[slot] = (kc[slot].float() * late_outlier).to(kc.dtype)
     ref = oc.window_attn(hp.f64(q), hp.f64(kc), hp.f64(vc), cu, q_pos, bt, n_q_heads, scale)
     if poison:
         # cache rows past every stream's frontier hold NaN: they must never influence a result
@@ -715,6 +724,86 @@ ATTN_CASES = [
     ("bf16", 2, 1, 128, [20] * 2100, [2] * 2100),             # more streams than the planner sorts
     ("bf16", 28, 4, 128, [300 + 7 * i for i in range(40)], [60 + i for i in range(40)]),   # > 512 work items
 ]
+
+
+# Rows whose maximum keeps moving: logits 4x / 8x wider than unit-scale data gives, or one key that
+# dominates late in the sweep.  The online softmax then raises its reference maximum after an item's
+# first tile (rescaling what it has accumulated), and the partial results of a split sweep meet with
+# maxima far apart.  Also the group sizes between the configurations' 4 and 7 and the largest one.
+ATTN_HARD_CASES = [
+    # dtype, Hq, Hkv, d, kv_lens, n_qs, scale_mult, late_outlier
+    ("bf16", 28, 4, 128, [915], [425], 4.0, 0.0),
+    ("bf16", 28, 4, 128, [915], [425], 8.0, 0.0),
+    ("bf16", 28, 4, 128, [6033], [300], 4.0, 0.0),               # split sweep, peaked rows
+    ("bf16", 28, 4, 128, [6033], [300], 1.0, 6.0),               # split sweep, the last key range dominates
+    ("bf16", 32, 8, 128, [700, 1300, 90], [300, 500, 60], 8.0, 0.0),
+    ("bf16", 32, 8, 128, [700, 1300, 90], [300, 500, 60], 1.0, 5.0),
+    ("bf16", 6, 2, 128, [800, 333], [200, 111], 1.0, 0.0),        # 3 query heads per kv head
+    ("bf16", 16, 1, 128, [1000], [260], 1.0, 0.0),                # 16 query heads per kv head
+    ("bf16", 16, 1, 128, [2500], [90], 4.0, 4.0),                 # ... split sweep, moving maximum
+    ("bf16", 48, 16, 64, [400, 200], [100, 64], 4.0, 0.0),        # d = 64 path, 3 per group
+    ("f32", 16, 1, 64, [300], [50], 8.0, 5.0),
+]
+
+
+@pytest.mark.parametrize("case", range(len(ATTN_HARD_CASES)))
+def test_window_prefill_attn_moving_maximum_and_group_sizes(cs, case):
+    dtype, hq, hkv, d, kv_lens, n_qs, mult, outlier = ATTN_HARD_CASES[case]
+    say(f"window_prefill_attn hard case {case}: {dtype} heads={hq}/{hkv} d={d} kv={kv_lens} n_q={n_qs} "
+        f"scale x{mult} outlier x{outlier}")
+    stats = _attn_case(cs, np.random.default_rng(3500 + case), dtype, hq, hkv, d, kv_lens, n_qs,
+                       scale_mult=mult, late_outlier=outlier)
+    say(f"  -> {stats}")
+
+
+@pytest.mark.parametrize("scale", [0.0, -0.1, float("inf"), float("nan")])
+def test_window_prefill_attn_rejects_bad_scale(cs, scale):
+    """A softmax scale that is not a positive finite number is an argument error (no launch)."""
+    say(f"window_prefill_attn: softmax_scale = {scale} is rejected")
+    z = torch.zeros((16, 4, 128), dtype=torch.bfloat16, device=DEV)
+    kc = torch.zeros((64, 1, 128), dtype=torch.bfloat16, device=DEV)
+    i32 = lambda v: torch.tensor(v, dtype=torch.int32, device=DEV)
+    wsb = cs.cs_window_prefill_attn_workspace(16, 1, 4, 1, 128, 4, cs.CS_BF16)
+    ws = torch.zeros((max(16, wsb),), dtype=torch.uint8, device=DEV)
+    with pytest.raises(cs.CodecSightError) as exc:
+        cs.cs_window_prefill_attn(z, kc, kc, i32([0, 16]), i32(list(range(16))), i32([64]), i32([[0, 1, 2, 3]]), 4, 16,
+                                  torch.zeros_like(z), 16, 1, 4, 1, 128, 128, 128, scale, cs.CS_BF16, ws, wsb)
+    assert exc.value.code == cs.CS_EINVAL
+
+
+def test_window_prefill_attn_clamps_the_frontier_to_kv_len(cs):
+    """A q_pos at or beyond its stream's kv_len is read as kv_len - 1: the call never indexes past
+    the rows the block table defines (the cache past them holds NaN here)."""
+    say("window_prefill_attn: q_pos beyond kv_len is clamped")
+    rng = np.random.default_rng(77)
+    hq, hkv, d, kv_len, n_q = 8, 2, 128, 200, 40
+    nb = -(-kv_len // 16)
+    bt = rng.permutation(nb + 5)[:nb].astype(np.int32)[None]
+    kc, vc = _pool(rng, ((nb + 5) * 16, hkv, d), "bf16"), _pool(rng, ((nb + 5) * 16, hkv, d), "bf16")
+    q = _pool(rng, (n_q, hq, d), "bf16")
+    q_pos = np.sort(rng.choice(kv_len, n_q, replace=False)).astype(np.int32)
+    bad = q_pos.copy()
+    bad[-3:] = [kv_len, kv_len + 500, 2 ** 30]                     # non-decreasing, out of range
+    good = q_pos.copy()
+    good[-3:] = kv_len - 1
+    cu = np.array([0, n_q], np.int32)
+    scale = 1.0 / math.sqrt(d)
+    ref = oc.window_attn(hp.f64(q), hp.f64(kc), hp.f64(vc), cu, good, bt, hq, scale)
+    used = np.zeros((nb + 5) * 16, bool)
+    j = np.arange(kv_len)
+    used[bt[0, j // 16] * 16 + j % 16] = True
+    kc[torch.from_numpy(~used)] = float("nan")
+    vc[torch.from_numpy(~used)] = float("nan")
+    for dtype, code in (("bf16", cs.CS_BF16),):
+        out = torch.zeros((n_q, hq, d), dtype=torch.bfloat16, device=DEV)
+        wsb = cs.cs_window_prefill_attn_workspace(n_q, 1, hq, hkv, d, nb, code)
+        ws = torch.zeros((max(16, wsb),), dtype=torch.uint8, device=DEV)
+        kd, vd = kc.to(DEV), vc.to(DEV)
+        cs.cs_window_prefill_attn(q.to(DEV), kd, vd, torch.from_numpy(cu).to(DEV), torch.from_numpy(bad).to(DEV),
+                                  torch.tensor([kv_len], dtype=torch.int32, device=DEV), torch.from_numpy(bt).to(DEV),
+                                  nb, 16, out, n_q, 1, hq, hkv, d, kd.stride(0), kd.stride(1), scale, code, ws, wsb)
+        torch.cuda.synchronize()
+        say(f"  -> {hp.check_attention(out.cpu(), ref, dtype)}")
 
 
 @pytest.mark.parametrize("case", range(len(ATTN_CASES)))
@@ -983,9 +1072,10 @@ def test_plan_refresh_matches_the_host_planner_on_a_workload(cs):
 
 
 # =============================================================================== whole step
-def _oracle_step(data_o: engine.StepData, layers):
-    """b -> c -> d with oracle pieces on host copies of the inputs; returns per-layer results."""
-    w, p = data_o.workload, data_o.plan
+def _oracle_step(data_o: engine.StepData, p: hp.OraclePlan, layers):
+    """b -> c -> d with oracle pieces on host copies of the inputs, on the plan oracle's row lists;
+    returns per-layer results."""
+    w = data_o.workload
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     k_pool, v_pool = data_o.k_pool.clone(), data_o.v_pool.clone()
     k_rows, v_rows = oc.rerotate(hp.f64(k_pool[layers]), hp.f64(v_pool[layers]), p.src_slot, p.dst_slot,
@@ -999,7 +1089,7 @@ def _oracle_step(data_o: engine.StepData, layers):
         oc.scatter(k_pool[layer].view(raw).numpy(), data_o.k_new[layer].view(raw).numpy(), p.q_slot)
         oc.scatter(v_pool[layer].view(raw).numpy(), data_o.v_new[layer].view(raw).numpy(), p.q_slot)
         outs[layer] = oc.window_attn(hp.f64(data_o.q[layer]), hp.f64(k_pool[layer]), hp.f64(v_pool[layer]),
-                                     p.cu_q, p.q_pos, p.layout.block_table, w.n_q_heads, data_o.softmax_scale)
+                                     p.cu_q, p.q_pos, p.block_table, w.n_q_heads, data_o.softmax_scale)
     return k_rows, k_pool, v_pool, outs
 
 
@@ -1019,14 +1109,18 @@ def test_whole_step_against_oracle(cs, wi):
     say(f"whole step: {w.name} streams={w.n_streams} layers={w.n_layers}")
     data_g = engine.assemble_step(w, engine.hip_scorer, device="cpu")
     data_o = engine.assemble_step(w, hp.oracle_scorer, device="cpu")
-    # (a) the two assemblies agree bit for bit, hence so do the plans
-    for name in ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "cu_q", "kv_len"):
-        assert np.array_equal(getattr(data_g.plan, name), getattr(data_o.plan, name)), name
+    # (a) the two assemblies agree bit for bit (history scoring on the GPU vs the oracle)
+    assert np.array_equal(data_g.old_layout.counts, data_o.old_layout.counts)
+    assert np.array_equal(data_g.new_layout.counts, data_o.new_layout.counts)
+    assert np.array_equal(data_g.new_layout.block_table, data_o.new_layout.block_table)
     assert np.array_equal(data_g.acc_in, data_o.acc_in)
     say(f"  sizes: {data_g.info}")
+    plan = hp.OraclePlan(data_o)
     step = engine.DeviceStep(data_g)
     step.run()
     torch.cuda.synchronize()
+    assert step.scoring_status() == 0
+    hp.assert_device_plan(step, plan)                         # (p) the refresh plan, entry for entry
     # (a) on the step's own frames
     keep_w, idx_w, off_w, acc_w = hp.oracle_scorer(data_o.mv, data_o.sad, data_o.frame_type, data_o.cu_frames,
                                                    data_o.acc_in, w, w.tau_mv_sq, w.tau_sad)
@@ -1035,12 +1129,12 @@ def test_whole_step_against_oracle(cs, wi):
     assert np.array_equal(step.kept_idx.cpu().numpy()[: idx_w.size], idx_w)
     assert np.array_equal(step.acc.cpu().numpy() != 0, acc_w != 0)
     layers = list(range(w.n_layers))
-    k_rows, k_pool_o, v_pool_o, outs = _oracle_step(data_o, layers)
-    dst = torch.from_numpy(data_o.plan.dst_slot.astype(np.int64))
+    k_rows, k_pool_o, v_pool_o, outs = _oracle_step(data_o, plan, layers)
+    dst = torch.from_numpy(plan.dst_slot.astype(np.int64))
     got_rows = step.k_pool.cpu()[:, dst].permute(1, 0, 2, 3).contiguous()
     say(f"  rerotate: {hp.check_rerotated(got_rows, k_rows, w.dtype)}")
     # (c) executed rows are bit-equal to the new K/V; values of reused rows are bit-equal copies
-    qs = torch.from_numpy(data_o.plan.q_slot.astype(np.int64))
+    qs = torch.from_numpy(plan.q_slot.astype(np.int64))
     assert torch.equal(step.k_pool.cpu()[:, qs], data_o.k_new) and torch.equal(step.v_pool.cpu()[:, qs], data_o.v_new)
     assert torch.equal(step.v_pool.cpu(), v_pool_o)
     for layer in layers:
@@ -1056,7 +1150,7 @@ def test_device_planned_step_equals_host_planned_step(cs, wi, slack):
     w = STEP_WORKLOADS[wi]
     say(f"device-planned step: {w.name} streams={w.n_streams} layers={w.n_layers} slack={slack}")
     data = engine.assemble_step(w, engine.hip_scorer, device="cpu")
-    host = engine.DeviceStep(data)
+    host = engine.DeviceStep(data, host_plan=True)
     host.run()
     n_reuse, n_q = data.info["n_reuse"], data.info["n_q"]
     devp = engine.DevicePlannedStep(data, reuse_cap=n_reuse + slack, q_cap=n_q + slack)
@@ -1157,28 +1251,38 @@ FULL_WORKLOADS = [synth.CFG1, synth.CFG2, synth.CFG3P, synth.CFG3D, synth.CFG4]
 
 @pytest.mark.parametrize("wi", range(len(FULL_WORKLOADS)))
 def test_full_size_step_sampled(cs, wi):
-    """The benchmark's own launch configuration at full size; the oracle checks (a) completely and
-    (b), (c), (d) on sampled rows / queries.  Big tensors are drawn on the GPU by torch's generator
-    and the sampled rows are copied to the host for the oracle."""
+    """The benchmark's own launch configuration at full size (the step bench.py times: refresh plan
+    made on the GPU, lists padded to capacities 1/8 above the row counts); the oracle checks (a) and
+    the plan completely, (c) completely, and (b), (d) on sampled rows / queries.  The queries are
+    drawn by the attention call's own decomposition: at least one from every 128-row tile of every
+    (stream, kv head) pair, every query head of it evaluated, plus each stream's first and last
+    query, so that every work item of the launch (and every key range of a split sweep) contributes
+    to a checked row; the first, a middle and the last layer are checked (the middle and last ones
+    reuse the first layer's work plan).  Big tensors are drawn on the GPU by torch's generator and
+    the sampled rows are copied to the host for the oracle."""
     w = FULL_WORKLOADS[wi]
     say(f"full-size step: {w.name}")
     data = engine.assemble_step(w, engine.hip_scorer, device=DEV)
     data_o = engine.assemble_step(w, hp.oracle_scorer, device="cpu", with_tensors=False)
-    for name in ("src_slot", "dst_slot", "delta", "q_pos", "q_slot", "cu_q", "kv_len"):
-        assert np.array_equal(getattr(data.plan, name), getattr(data_o.plan, name)), name
+    assert np.array_equal(data.old_layout.counts, data_o.old_layout.counts)
+    assert np.array_equal(data.new_layout.counts, data_o.new_layout.counts)
+    assert np.array_equal(data.new_layout.block_table, data_o.new_layout.block_table)
     say(f"  sizes: {data.info}")
-    p = data.plan
+    p = hp.OraclePlan(data_o)                                   # row lists from the plan oracle
     rng = np.random.default_rng(900 + wi)
     k_before = data.k_pool.clone()
     v_before = data.v_pool.clone()
-    step = engine.DeviceStep(data)
+    cap = lambda n: (n + n // 8 + 255) // 256 * 256
+    step = engine.DeviceStep(data, reuse_cap=cap(data.info["n_reuse"]), q_cap=cap(data.info["n_q"]))
     step.run()
     torch.cuda.synchronize()
+    assert step.scoring_status() == 0
     keep_w, idx_w, off_w, _ = hp.oracle_scorer(data.mv, data.sad, data.frame_type, data.cu_frames, data.acc_in,
                                                w, w.tau_mv_sq, w.tau_sad)
     assert np.array_equal(step.keep.cpu().numpy(), keep_w)
     assert np.array_equal(step.kept_off.cpu().numpy(), off_w)
     assert np.array_equal(step.kept_idx.cpu().numpy()[: idx_w.size], idx_w)
+    hp.assert_device_plan(step, p)
     # (b) sampled reused rows, all layers
     n_rows = int(p.src_slot.size)
     pick = np.sort(rng.choice(n_rows, size=min(256, n_rows), replace=False))
@@ -1191,17 +1295,29 @@ def test_full_size_step_sampled(cs, wi):
     say(f"  rerotate ({pick.size} rows x {w.n_layers} layers): {hp.check_rerotated(got, k_ref, w.dtype)}")
     assert torch.equal(step.v_pool[:, dst], v_before[:, src])
     # (c) complete, bit exact (plain indexing is the definition)
+    n_q = int(p.q_pos.size)
     qs = torch.from_numpy(p.q_slot.astype(np.int64)).to(DEV)
-    assert torch.equal(step.k_pool[:, qs], step.k_new) and torch.equal(step.v_pool[:, qs], step.v_new)
+    assert torch.equal(step.k_pool[:, qs], step.k_new[:, :n_q]) and torch.equal(step.v_pool[:, qs], step.v_new[:, :n_q])
     # rows that are neither a destination nor a refresh target are untouched
     touched = torch.zeros(data.n_slots, dtype=torch.bool, device=DEV)
     touched[qs] = True
     touched[torch.from_numpy(p.dst_slot.astype(np.int64)).to(DEV)] = True
     assert torch.equal(step.k_pool[:, ~touched], k_before[:, ~touched])
-    # (d) sampled queries of two layers, every head; the oracle reads the cache the GPU attention read
-    n_q = int(p.q_pos.size)
-    rows = np.sort(rng.choice(n_q, size=min(40, n_q), replace=False))
-    for layer in (0, w.n_layers - 1):
+    assert not step.out[:, n_q:].any()                           # rows past the executed rows are not written
+    # (d) queries stratified by row tile, every head; the oracle reads the cache the method defines
+    group = w.n_q_heads // w.n_kv_heads
+    rows = []
+    for s in range(w.n_streams):
+        q0, q1 = int(p.cu_q[s]), int(p.cu_q[s + 1])
+        if q1 == q0:
+            continue
+        rows += [q0, q1 - 1]
+        n_r = (q1 - q0) * group
+        for t0 in range(0, n_r, 128):
+            r = int(rng.integers(t0, min(t0 + 128, n_r)))
+            rows.append(q0 + r // group)
+    rows = np.unique(np.asarray(rows, np.int64))
+    for layer in sorted({0, w.n_layers // 2, w.n_layers - 1}):
         # cache for the oracle: reused rows re-rotated by the ORACLE (rounded), refresh rows from k_new
         s_of = np.searchsorted(p.cu_q, rows, side="right") - 1
         ref = np.zeros((rows.size, w.n_q_heads, w.head_dim))
@@ -1209,7 +1325,7 @@ def test_full_size_step_sampled(cs, wi):
             sel = rows[s_of == s]
             n_ctx = int(p.q_pos[sel].max()) + 1
             j = np.arange(n_ctx)
-            slots = p.layout.block_table[s, j // 16].astype(np.int64) * 16 + j % 16
+            slots = p.block_table[s, j // 16].astype(np.int64) * 16 + j % 16
             kk = _oracle_cache_rows(k_before[layer], step.k_new[layer], p, slots, w, rotate=True)
             vv = _oracle_cache_rows(v_before[layer], step.v_new[layer], p, slots, w, rotate=False)
             bt_local = np.arange(-(-n_ctx // 16), dtype=np.int32)[None]
@@ -1220,7 +1336,8 @@ def test_full_size_step_sampled(cs, wi):
             ref[s_of == s] = oc.window_attn(q_sel, kk, vv, np.array([0, sel.size], np.int32), p.q_pos[sel],
                                             bt_local, w.n_q_heads, data.softmax_scale)
         got = step.out[layer][torch.from_numpy(rows.astype(np.int64)).to(DEV)].cpu()
-        say(f"  attention layer {layer} ({rows.size} queries): {hp.check_attention(got, ref, w.dtype)}")
+        say(f"  attention layer {layer} ({rows.size} queries x {w.n_q_heads} heads): "
+            f"{hp.check_attention(got, ref, w.dtype)}")
 
 
 def _oracle_cache_rows(pool_before, new_rows, plan, slots, w, rotate):

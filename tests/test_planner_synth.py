@@ -295,3 +295,32 @@ def test_decoded_frames_are_seeded_and_differ_where_the_scene_changes():
     assert np.array_equal(cur, cur2) and np.array_equal(prev, prev2)
     diff = np.abs(cur[0].astype(int) - prev[0].astype(int))
     assert 1.0 < diff.mean() < 40.0 and np.median(diff) <= 2
+
+
+def test_plan_batch_is_plan_stream_per_stream():
+    """The batch form of the plan oracle is the per-stream plan of every stream, lists concatenated
+    stream-major with cu_q marking the executed rows of each stream."""
+    from oracle import plan_oracle as po
+    rng = np.random.default_rng(5)
+    n_streams, window, stride, t_per, n_text = 3, 6, 2, 9, 4
+    old_types = (rng.random((n_streams, window)) < 0.3).astype(np.uint8)
+    old_counts = rng.integers(0, t_per + 1, (n_streams, window)).astype(np.int32)
+    old_counts[old_types == 1] = t_per
+    new_types = (rng.random((n_streams, stride)) < 0.3).astype(np.uint8)
+    new_counts = rng.integers(0, t_per + 1, (n_streams, stride)).astype(np.int32)
+    bt_old = rng.permutation(24).reshape(n_streams, 8).astype(np.int32)
+    bt_new = (24 + rng.permutation(24)).reshape(n_streams, 8).astype(np.int32)
+    got = po.plan_batch(old_types.tolist(), old_counts.tolist(), new_types.tolist(), new_counts.tolist(), n_text,
+                        t_per, bt_old, bt_new)
+    at_r = at_q = 0
+    for s in range(n_streams):
+        one = po.plan_stream(old_types[s].tolist(), old_counts[s].tolist(), new_types[s].tolist(),
+                             new_counts[s].tolist(), n_text, t_per, bt_old[s], bt_new[s])
+        n_r, n_q = len(one["src_slot"]), len(one["q_pos"])
+        for k in ("src_slot", "dst_slot", "delta"):
+            assert got[k][at_r: at_r + n_r] == one[k]
+        for k in ("q_pos", "q_slot", "q_kind"):
+            assert got[k][at_q: at_q + n_q] == one[k]
+        assert got["cu_q"][s] == at_q and got["cu_q"][s + 1] == at_q + n_q and got["kv_len"][s] == one["kv_len"]
+        at_r, at_q = at_r + n_r, at_q + n_q
+    assert len(got["src_slot"]) == at_r and len(got["q_pos"]) == at_q
