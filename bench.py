@@ -330,7 +330,7 @@ def cpu_baseline(w, data, step, k_rows_before, pick, torch):
             n_rot = min(max_rot, pick.size)
             t0 = time.perf_counter()
             if n_rot:
-                oc.rotate(k_host[:, :n_rot], p.delta[pick[:n_rot]].astype(np.float64)[None, :, None, None], w.rope_base)
+                oc.rotate(k_host[:, :n_rot], p.delta[pick[:n_rot]].astype(np.float64)[None, :, None], w.rope_base)
             t_b = (time.perf_counter() - t0) * rows / max(1, n_rot)
             t0 = time.perf_counter()
             oc.scatter(k_l, kn, p.q_slot)
