@@ -200,6 +200,27 @@ int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intr
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * (a') cs_score_compact for callers that cannot allocate device memory or pass a workspace: code
+ *     under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * Same arguments, results and errors as cs_score_compact, without the workspace: the look-back words
+ * live in an array the library holds in device memory of each GPU (8,448 bytes per GPU, kept until
+ * the process ends).  Limit: n_streams <= 4096 (CS_EUNSUPPORTED beyond: use cs_score_compact).
+ * The call allocates nothing and calls no allocating routine; its first call on a device looks up
+ * the array's address (make that call outside a graph capture).  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (different streams) race and must be
+ * serialised by the caller; back-to-back calls on one stream are fine (each call clears what it
+ * needs with a kernel of its own, whatever the previous call left).  The device status word
+ * described above is not readable through this entry point.
+ * ------------------------------------------------------------------------------------------ */
+int cs_score_compact_noalloc(const int16_t* mv, const uint32_t* sad, const uint8_t* intra,
+                             const uint8_t* frame_type, const int32_t* cu_frames, uint8_t* acc_mask,
+                             int32_t n_streams, int32_t n_frames,
+                             int32_t grid_h, int32_t grid_w, int32_t group,
+                             uint32_t tau_mv_sq, uint32_t tau_sad, int32_t use_residual,
+                             uint8_t* keep_mask, int32_t* kept_idx, int32_t* kept_off, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * (p) Refresh plan on the device.     Paper Sec. 3.4.1 (overlap I-frames are anchors and are
  *     recomputed, the other overlap frames reuse their cached K/V, new frames and the text
  *     suffix are prefilled) and Sec. 3.5 (planning precedes KV-context preparation; a frame-aware

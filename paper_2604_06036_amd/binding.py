@@ -27,6 +27,7 @@ _ERR = {CS_EINVAL: "CS_EINVAL", CS_EUNSUPPORTED: "CS_EUNSUPPORTED", CS_EHIP: "CS
         CS_EWORKSPACE: "CS_EWORKSPACE"}
 
 EXPORTS = ("cs_version", "cs_last_hip_error", "cs_project_blocks", "cs_residual_proxy", "cs_score_compact_workspace", "cs_score_compact",
+           "cs_score_compact_noalloc",
            "cs_plan_refresh_workspace", "cs_plan_refresh", "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
            "cs_window_prefill_attn_workspace",
            "cs_window_prefill_attn")
@@ -63,6 +64,9 @@ def lib() -> ctypes.CDLL:
     L.cs_score_compact.restype = c.c_int
     L.cs_score_compact.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, u32, u32, i32,
                                    vp, vp, vp, vp, sz, vp]
+    L.cs_score_compact_noalloc.restype = c.c_int
+    L.cs_score_compact_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, u32, u32, i32,
+                                           vp, vp, vp, vp]
     L.cs_project_blocks.restype = c.c_int
     L.cs_project_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     L.cs_residual_proxy.restype = c.c_int
@@ -145,6 +149,21 @@ def cs_score_compact(mv, sad, intra, frame_type, cu_frames, acc_mask, n_streams,
         _ptr(mv), _ptr(sad), _ptr(intra), _ptr(frame_type), _ptr(cu_frames), _ptr(acc_mask),
         n_streams, n_frames, grid_h, grid_w, group, tau_mv_sq, tau_sad, int(bool(use_residual)),
         _ptr(keep_mask), _ptr(kept_idx), _ptr(kept_off), _ptr(workspace), workspace_bytes, _stream()))
+
+
+def cs_score_compact_noalloc(mv, sad, intra, frame_type, cu_frames, acc_mask, n_streams, n_frames, grid_h,
+                             grid_w, group, tau_mv_sq, tau_sad, use_residual, keep_mask, kept_idx, kept_off):
+    fn = "cs_score_compact_noalloc"
+    n_patch, n_tok = grid_h * grid_w, (grid_h // max(1, group)) * (grid_w // max(1, group))
+    _need(fn, mv, n_frames * n_patch * 2, "mv"); _need(fn, sad, n_frames * n_patch, "sad")
+    _need(fn, intra, n_frames * n_patch, "intra"); _need(fn, frame_type, n_frames, "frame_type")
+    _need(fn, cu_frames, n_streams + 1, "cu_frames"); _need(fn, acc_mask, n_streams * n_patch, "acc_mask")
+    _need(fn, keep_mask, n_frames * n_tok, "keep_mask"); _need(fn, kept_idx, n_frames * n_tok, "kept_idx")
+    _need(fn, kept_off, n_frames + 1, "kept_off")
+    _check(fn, lib().cs_score_compact_noalloc(
+        _ptr(mv), _ptr(sad), _ptr(intra), _ptr(frame_type), _ptr(cu_frames), _ptr(acc_mask),
+        n_streams, n_frames, grid_h, grid_w, group, tau_mv_sq, tau_sad, int(bool(use_residual)),
+        _ptr(keep_mask), _ptr(kept_idx), _ptr(kept_off), _stream()))
 
 
 CS_SCORE_STATUS_OFFSET = 4

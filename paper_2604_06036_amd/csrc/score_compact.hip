@@ -20,6 +20,8 @@
 //           and write their dense ids at base + rank.
 // The look-back wait is bounded: after kSpinLimit polls a tile raises the error word in the
 // workspace and continues with a zero prefix, so every wave always exits.
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -568,13 +570,22 @@ extern "C" size_t cs_score_compact_workspace(int32_t n_streams, int32_t n_frames
   return (static_cast<size_t>(tiles_for(n_streams)) + 1) * sizeof(uint64_t);
 }
 
-extern "C" int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intra,
-                                const uint8_t* frame_type, const int32_t* cu_frames,
-                                uint8_t* acc_mask, int32_t n_streams, int32_t n_frames,
-                                int32_t grid_h, int32_t grid_w, int32_t group,
-                                uint32_t tau_mv_sq, uint32_t tau_sad, int32_t use_residual,
-                                uint8_t* keep_mask, int32_t* kept_idx, int32_t* kept_off,
-                                void* workspace, size_t workspace_bytes, void* stream) {
+// Scratch of the entry point that allocates nothing (cs_score_compact_noalloc): the look-back words
+// of the one-launch form for up to 4,096 streams ((1,024 tiles + 1) x 8 bytes).  Every GPU the
+// library runs on holds its own copy, at its own address, until the process ends; host code reaches
+// it only through the pointer hipGetSymbolAddress returns for the current device.
+constexpr size_t kNoAllocScratchBytes = 8448;
+static __device__ __align__(256) unsigned char g_score_scratch[kNoAllocScratchBytes];
+
+namespace {
+
+int score_compact_call(const int16_t* mv, const uint32_t* sad, const uint8_t* intra,
+                       const uint8_t* frame_type, const int32_t* cu_frames,
+                       uint8_t* acc_mask, int32_t n_streams, int32_t n_frames,
+                       int32_t grid_h, int32_t grid_w, int32_t group,
+                       uint32_t tau_mv_sq, uint32_t tau_sad, int32_t use_residual,
+                       uint8_t* keep_mask, int32_t* kept_idx, int32_t* kept_off,
+                       void* workspace, size_t workspace_bytes, void* stream) {
   if (n_streams < 0 || n_frames < 0 || grid_h < 1 || grid_w < 1 || group < 1) return CS_EINVAL;
   if (group != 1 && group != 2) return CS_EUNSUPPORTED;
   if (grid_h % group || grid_w % group) return CS_EINVAL;
@@ -654,4 +665,61 @@ extern "C" int cs_score_compact(const int16_t* mv, const uint32_t* sad, const ui
   }
 #undef CS_LAUNCH_SCORE
   return cs::note_hip(hipGetLastError());
+}
+
+// The entry point that allocates nothing serves up to kNoAllocMaxStreams streams.
+constexpr int kNoAllocMaxStreams = kFusedMaxStreams;
+static_assert((kFusedMaxStreams / kWavesPerTile + 1) * sizeof(uint64_t) <= kNoAllocScratchBytes, "scratch too small");
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the scratch array on the current device (resolved once per device).
+int score_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return cs::note_hip(e);
+  if (dev < 0 || dev >= kMaxDevices) return CS_EUNSUPPORTED;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_score_scratch));
+    if (e != hipSuccess || !ptr) return cs::note_hip(e == hipSuccess ? hipErrorInvalidSymbol : e);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CS_OK;
+}
+
+}  // namespace
+
+extern "C" int cs_score_compact(const int16_t* mv, const uint32_t* sad, const uint8_t* intra,
+                                const uint8_t* frame_type, const int32_t* cu_frames,
+                                uint8_t* acc_mask, int32_t n_streams, int32_t n_frames,
+                                int32_t grid_h, int32_t grid_w, int32_t group,
+                                uint32_t tau_mv_sq, uint32_t tau_sad, int32_t use_residual,
+                                uint8_t* keep_mask, int32_t* kept_idx, int32_t* kept_off,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  return score_compact_call(mv, sad, intra, frame_type, cu_frames, acc_mask, n_streams, n_frames, grid_h, grid_w,
+                            group, tau_mv_sq, tau_sad, use_residual, keep_mask, kept_idx, kept_off, workspace,
+                            workspace_bytes, stream);
+}
+
+extern "C" int cs_score_compact_noalloc(const int16_t* mv, const uint32_t* sad, const uint8_t* intra,
+                                        const uint8_t* frame_type, const int32_t* cu_frames,
+                                        uint8_t* acc_mask, int32_t n_streams, int32_t n_frames,
+                                        int32_t grid_h, int32_t grid_w, int32_t group,
+                                        uint32_t tau_mv_sq, uint32_t tau_sad, int32_t use_residual,
+                                        uint8_t* keep_mask, int32_t* kept_idx, int32_t* kept_off,
+                                        void* stream) {
+  if (n_streams > kNoAllocMaxStreams) return CS_EUNSUPPORTED;      // beyond the static scratch
+  void* scratch = nullptr;
+  const int e = score_scratch(&scratch);
+  if (e != CS_OK) return e;
+  // the one-launch form clears the look-back words it uses with a kernel of its own on `stream`,
+  // so the contents the previous call left in the scratch never matter
+  return score_compact_call(mv, sad, intra, frame_type, cu_frames, acc_mask, n_streams, n_frames, grid_h, grid_w,
+                            group, tau_mv_sq, tau_sad, use_residual, keep_mask, kept_idx, kept_off, scratch,
+                            kNoAllocScratchBytes, stream);
 }
