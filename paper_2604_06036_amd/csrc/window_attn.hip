@@ -29,16 +29,6 @@
 
 #include "common.h"
 
-#ifndef CS_X_SWAP
-#define CS_X_SWAP 1
-#endif
-#ifndef CS_X_ADDR
-#define CS_X_ADDR 1
-#endif
-#ifndef CS_X_WNUM
-#define CS_X_WNUM 4
-#define CS_X_WDEN 3
-#endif
 
 namespace {
 
@@ -65,7 +55,7 @@ struct AttnParams {
   // shared by several work items; their un-normalised partial results go to the workspace and a
   // second kernel merges them (merging in the last workgroup to finish was tried and is far
   // slower here: the device-scope release/acquire it needs writes back and invalidates the L2)
-  int32_t chunk_tiles, max_splits, bm;
+  int32_t chunk_tiles, max_splits, bm, span;
   const int32_t* ws_plan;   // plan header (list offsets per XCD, row-tile count, end item, first items)
   const int32_t* ws_items;  // item descriptors, 8 ints each, the 8 XCD lists back to back
   int32_t* ws_desc;      // [items][8]: q0, rows_total, r_tile, kvh, n_split
@@ -426,6 +416,9 @@ struct PlanParams {
   int32_t* rt_stream;   // [r_cap]
   int32_t* rt_wgmax;    // [r_cap]
   int32_t* hist;        // [8][hist_pitch] items per (XCD, bucket), then list cursors
+  int32_t span;         // 1: sweeps are cut into contiguous spans of equal cost (few, long sweeps)
+  int32_t pref_pitch;   // ints per XCD in sw_pref
+  int32_t* sw_pref;     // [8][pref_pitch] span plan: cost prefix of each XCD's sweeps
 };
 
 // Exclusive prefix sum over the kPlanThreads threads of the planning workgroup.
@@ -461,11 +454,177 @@ __device__ __forceinline__ int plan_xcd_of_pair(int pair) {
   return (round & 1) ? 7 - pos : pos;
 }
 
+// Span plan, for launches with few (row tile, kv head) sweeps, some of them long (one stream with
+// a long window; any small batch).  Dealing whole sweeps, or fixed key ranges of them, to workgroups
+// leaves the workgroups with unequal totals because the pieces are coarse next to a workgroup's
+// share.  Here every XCD gets every eighth sweep (sweep = row tile * kv heads + kv head, so with
+// four or eight kv heads an XCD serves one kv head), lays its sweeps end to end, and the sequence
+// is cut into one contiguous span per workgroup, of equal COST: 2 n_kt + kItemFixedCostHalves per
+// sweep, in half key tiles, the second workgroup of a CU (slots 32..63) getting 3/4 of the first
+// one's share because the issue arbiter serves it less often.  A sweep that a cut crosses becomes
+// several items whose partial results the merge kernel combines; cuts closer than kMinPieceTiles to
+// a sweep's end move onto it.  Items of a workgroup are consecutive in the list, pieces of a sweep
+// are consecutive too, and the position of an item in the list also names its partial-result slot.
+constexpr int kMinSpanTiles = 3;     // fewer workgroups are used rather than give one less than this
+constexpr int kMinPieceTiles = 2;
+constexpr int kSpanWeightFirst = 4, kSpanWeightSecond = 3;
+
+constexpr int kSpanPrefInLds = 8 * 136;   // the span plan runs with fewer than 1,024 sweeps: at most 130 ints per XCD
+
+__device__ void plan_spans(const PlanParams& pp, int n_rt, int* s_wave, int (*s_cut)[kSlotsPerXcd + 1], int* s_pref) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n_kv = pp.n_kv_heads;
+  const int n_sw = n_rt * n_kv;
+  auto sweep_tiles = [&](int sw) { return max(pp.rt_wgmax[sw / n_kv], 0) / kBN + 1; };
+  // ---- cost prefix of every XCD's sweeps (one wave per XCD)
+  if (w < 8) {
+    int32_t* pref = pp.sw_pref + w * pp.pref_pitch;
+    const int n_x = (n_sw - w + 7) >> 3;
+    int run = 0;
+    if (lane == 0) pref[0] = 0;
+    for (int i0 = 0; i0 < n_x; i0 += 64) {
+      const int i = i0 + lane;
+      const int v = i < n_x ? 2 * sweep_tiles(8 * i + w) + kItemFixedCostHalves : 0;
+      int incl = v;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+      }
+      if (i < n_x) pref[i + 1] = run + incl;
+      run += __shfl(incl, 63);
+    }
+  }
+  __threadfence_block();
+  __syncthreads();
+  // the searches below read the prefixes many times: keep them in LDS when they fit (they do for
+  // every launch the host routes here; the global copy serves the general case)
+  const bool in_lds = 8 * pp.pref_pitch <= kSpanPrefInLds;
+  if (in_lds)
+    for (int i = tid; i < 8 * pp.pref_pitch; i += kPlanThreads)
+      s_pref[i] = __hip_atomic_load(&pp.sw_pref[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  // Position helpers of XCD x.  A position is a tile count from the start of the XCD's sequence.
+  auto n_of = [&](int x) { return (n_sw - x + 7) >> 3; };
+  auto cost_pref = [&](int x, int i) {
+    return in_lds ? s_pref[x * pp.pref_pitch + i]
+                  : __hip_atomic_load(&pp.sw_pref[x * pp.pref_pitch + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
+  auto tile_pref = [&](int x, int i) { return (cost_pref(x, i) - kItemFixedCostHalves * i) >> 1; };
+  auto sweep_at_tile = [&](int x, int pos) {      // largest i with tile_pref(i) <= pos (pos < total tiles)
+    int lo = 0, hi = n_of(x);
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (tile_pref(x, mid) <= pos) lo = mid; else hi = mid;
+    }
+    return lo;
+  };
+  // ---- cuts: thread (x, j) places the start of workgroup j's span
+  const int x = tid >> 6, j = tid & 63;          // threads 0..511: one per (XCD, workgroup)
+  const int n_wg = min(pp.n_slots, kSlotsPerXcd);
+  if (tid < 512) {
+    const int n_x = n_of(x);
+    const int total_tiles = n_x > 0 ? tile_pref(x, n_x) : 0;
+    const int total_cost = n_x > 0 ? cost_pref(x, n_x) : 0;
+    const int spans = total_tiles > 0 ? max(1, min(n_wg, total_tiles / kMinSpanTiles)) : 0;
+    auto weight_before = [&](int k) { return k <= 32 ? kSpanWeightFirst * k : kSpanWeightFirst * 32 + kSpanWeightSecond * (k - 32); };
+    int cut = total_tiles;
+    if (j < spans) {
+      const int64_t c = static_cast<int64_t>(total_cost) * weight_before(j) / weight_before(spans);   // cost position
+      int lo = 0, hi = n_x;                       // largest i with cost_pref(i) <= c
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cost_pref(x, mid) <= c) lo = mid; else hi = mid;
+      }
+      const int len = sweep_tiles(8 * lo + x);
+      int o = static_cast<int>(c - cost_pref(x, lo) - kItemFixedCostHalves + 1) >> 1;
+      o = max(0, min(o, len));
+      if (o < kMinPieceTiles) o = 0;
+      if (len - o < kMinPieceTiles) o = len;
+      cut = j == 0 ? 0 : tile_pref(x, lo) + o;
+    }
+    s_cut[x][j] = cut;
+    if (j == 0) s_cut[x][kSlotsPerXcd] = total_tiles;
+  }
+  __syncthreads();
+  // ---- items per workgroup, their positions in the list
+  int i_lo = 0, i_hi = -1, lo_t = 0, hi_t = 0;
+  if (tid < 512) {
+    lo_t = s_cut[x][j];
+    hi_t = s_cut[x][j + 1];
+    if (hi_t > lo_t) {
+      i_lo = sweep_at_tile(x, lo_t);
+      i_hi = sweep_at_tile(x, hi_t - 1);
+    }
+  }
+  const int count = i_hi - i_lo + 1;
+  int total_items;
+  const int first = plan_block_scan(tid < 512 ? count : 0, s_wave, total_items);
+  if (tid < 512 && j == 0) pp.header[x] = first;
+  if (tid == 0) {
+    pp.header[8] = total_items;
+    pp.header[9] = n_sw;
+    for (int i = 10; i < kHdrHeads; ++i) pp.header[i] = 0;
+    pp.header[kHdrEndItem + 4] = -1;                    // end item: no key tiles, nothing visible
+    pp.header[kHdrEndItem + 6] = -1;
+    pp.header[kHdrEndItem + 7] = -1;
+  }
+  for (int i = n_sw + tid; i < pp.r_cap * n_kv; i += kPlanThreads)
+    pp.rt_desc[static_cast<int64_t>(i) * 8 + 4] = 0;
+  if (tid >= 512) return;
+  // ---- write the items of workgroup (x, j) and its header entry
+  int32_t d_first[8] = {0, 0, 0, 0, -1, 0, -1, -1};     // the end item
+  for (int i = i_lo; i <= i_hi; ++i) {
+    const int sw = 8 * i + x;
+    const int r = sw / n_kv, kvh = sw - r * n_kv;
+    const int s = pp.rt_stream[r];
+    const int t = r - pp.st_toff[s];
+    const int q0 = pp.cu_q[s];
+    const int rows = plan_stream_rows(pp, s);
+    const int wg_max = pp.rt_wgmax[r];
+    const int begin = tile_pref(x, i), n_kt = tile_pref(x, i + 1) - begin;
+    const int kb = max(lo_t, begin) - begin, ke = min(hi_t, begin + n_kt) - begin;
+    const int pos = first + (i - i_lo);
+    const bool split = kb > 0 || ke < n_kt;
+    int32_t d[8] = {q0, rows, t * pp.bm, kvh | (s << 8), wg_max, kb | (ke << 16), i < i_hi ? pos + 1 : -1,
+                    split ? pos * pp.bm : -1};
+    int32_t* it = pp.items + static_cast<int64_t>(pos) * 8;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) it[k] = d[k];
+    if (i == i_lo) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) d_first[k] = d[k];
+    }
+    if (kb == 0) {                                       // the sweep's first piece describes it to the merge kernel
+      int pieces = 1;
+      for (int k = 1; k < kSlotsPerXcd; ++k) {
+        const int c = s_cut[x][k];
+        pieces += (c > begin && c < begin + n_kt && c != s_cut[x][k - 1]) ? 1 : 0;
+      }
+      int32_t* rd = pp.rt_desc + static_cast<int64_t>(sw) * 8;
+      rd[0] = q0; rd[1] = rows; rd[2] = t * pp.bm; rd[3] = kvh; rd[4] = pieces; rd[5] = pos;
+    }
+  }
+  int32_t* hd = pp.header + kHdrHeads + kHdrEntryInts * (x * kSlotsPerXcd + j);
+  int32_t ids[4] = {0, 0, 0, 0}, last_id = 0;
+  if (count > 0) {
+    const int32_t* row = pp.block_table + static_cast<int64_t>(d_first[3] >> 8) * pp.max_blocks;
+    const int last_blk = max(d_first[4], 0) >> 4;
+    for (int i = 0; i < 4; ++i) ids[i] = row[min((d_first[5] & 0xffff) * 4 + i, last_blk)];
+    last_id = row[last_blk];
+  }
+  hd[0] = count > 0 ? first : -1; hd[1] = count > 1 ? first + 1 : -1; hd[2] = count > 2 ? first + 2 : -1; hd[3] = last_id;
+  for (int i = 0; i < 4; ++i) hd[4 + i] = ids[i];
+  for (int i = 0; i < 8; ++i) hd[8 + i] = d_first[i];
+  hd[16] = count;
+}
+
 __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanParams pp) {
   __shared__ int s_wave[kPlanThreads / 64];
   __shared__ unsigned long long s_key[kSortMax];
   __shared__ int s_list_off[9];
   __shared__ int s_by_rank[8][64];      // deal: lane (and length) of the item of each rank, per XCD
+  __shared__ int s_cut[8][kSlotsPerXcd + 1];   // span plan: first tile position of every workgroup's span
   const int tid = threadIdx.x;
   const int hist_pitch = pp.hist_pitch;
 
@@ -510,6 +669,11 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   }
   __threadfence_block();
   __syncthreads();
+
+  if (pp.span) {
+    plan_spans(pp, n_rt, s_wave, s_cut, reinterpret_cast<int*>(s_key));    // s_key is unused on this route
+    return;
+  }
 
   // ---- rank streams by decreasing work (ties: stream order)
   if (pp.n_streams <= kSortMax) {
@@ -690,11 +854,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
           if (taken == 2) first3[2] = idx;
           ++taken;
           last = idx;
-#ifdef CS_X_WNUM
-          load += (2 * (got >> 8) + kItemFixedCostHalves) * (lane >= 32 ? CS_X_WNUM : CS_X_WDEN);
-#else
-          load += 2 * (got >> 8) + kItemFixedCostHalves;
-#endif
+          load += (2 * (got >> 8) + kItemFixedCostHalves) * (lane >= 32 ? kSpanWeightFirst : kSpanWeightSecond);
         }
         __builtin_amdgcn_wave_barrier();
       }
@@ -720,12 +880,6 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
   }
 }
 
-#if CS_X_TS
-__device__ uint32_t g_ts[512 * 4 * 8];
-typedef __attribute__((ext_vector_type(2))) uint32_t ts_t;
-__device__ __forceinline__ ts_t ts_now() { ts_t v; asm volatile("s_memtime %0" : "=&s"(v)); return v; }
-#define TS_ADD(acc, a, b) acc += (b)[0] - (a)[0]
-#endif
 
 // Scalar loads issued by hand: the results are uniform, travel outside the vector-memory queue
 // (so waiting for them never drains tile requests) and are only read after the explicit wait.
@@ -756,21 +910,10 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   __shared__ __attribute__((aligned(1024))) uint16_t sK[2][TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t sV[2][TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t s_sink[4][512];   // see request_part
-#if CS_X_OCC1
-  __shared__ uint16_t s_pad[24576];
-  reinterpret_cast<volatile uint16_t*>(s_pad)[threadIdx.x] = 0;
-#endif
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
-#if CS_X_PRIO == 1
-  if (__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 4) & 1) __builtin_amdgcn_s_setprio(3);
-#elif CS_X_PRIO == 2
-  if ((blockIdx.x >> 8) & 1) __builtin_amdgcn_s_setprio(3);
-#elif CS_X_PRIO == 3
-  if ((blockIdx.x >> 3) & 1) __builtin_amdgcn_s_setprio(3);
-#endif
 
   // ---- this workgroup's items: a chain through the `next` field of the descriptors, dealt by the
   //      planning kernel; three descriptors of look-ahead are kept loaded
@@ -811,13 +954,11 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   for (int db = 0; db < DB; ++db)
     v_rd[db] = v_row * D + (((4 * db + 2 * gid + ((i16 & 3) >> 1)) ^ v_swz) << 3) + 4 * (i16 & 1);
 
-#if CS_X_ADDR
   uint32_t k_addr[STEPS], v_addr[DB];   // LDS byte addresses of this lane's fragments in stage 0
 #pragma unroll
   for (int st = 0; st < STEPS; ++st) k_addr[st] = lds_address(&sK[0][0]) + 2 * k_rd[st];
 #pragma unroll
   for (int db = 0; db < DB; ++db) v_addr[db] = lds_address(&sV[0][0]) + 2 * v_rd[db];
-#endif
 
   // ---- a slot of the tile stream: one key tile of one item, with the cache-block ids its
   //      request needs (this wave's quarter of the tile, and the block of the item's frontier)
@@ -962,20 +1103,14 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
 
   auto compute = [&](int kt, int stage) {
     const int j0 = kt * kBN;
-    const uint16_t* tK = sK[stage];
-    const uint16_t* tV = sV[stage];
     f32x16 sacc[RB][2];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#ifndef CS_X_KPF
-#define CS_X_KPF 2
-#endif
-#ifndef CS_X_VPF
-#define CS_X_VPF 3
-#endif
-    constexpr int KPF = CS_X_KPF;        // K fragments are read two steps ahead of their MFMAs
+    constexpr int KPF = 2;        // K fragments are read two steps ahead of their MFMAs
     bf16x8 ka[KPF + 1][2];
-#if CS_X_ADDR
     typedef __attribute__((address_space(3))) const cs::u32x4 lds_u32x4;
+    // LDS addresses of this tile's fragments: one add per address and tile; pinning them in
+    // registers lets every read fold its row-group offset into the instruction's immediate field
+    // (formed at each use they cost two vector instructions per pair of reads)
     const uint32_t stage_off = static_cast<uint32_t>(stage) * (TILE * 2);
     uint32_t kad[STEPS], va[DB];
 #pragma unroll
@@ -991,11 +1126,6 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
     auto k_frag = [&](int st, int kb) {
       return __builtin_bit_cast(bf16x8, reinterpret_cast<lds_u32x4*>(static_cast<uintptr_t>(kad[st]))[kb * 32 * D * 2 / 16]);
     };
-#else
-    auto k_frag = [&](int st, int kb) {
-      return __builtin_bit_cast(bf16x8, *reinterpret_cast<const cs::u32x4*>(&tK[kb * 32 * D + k_rd[st]]));
-    };
-#endif
 #pragma unroll
     for (int st = 0; st < KPF; ++st) {
       ka[st][0] = k_frag(st, 0);
@@ -1040,31 +1170,22 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) t_max = fmaxf(t_max, sacc[rb][kb][r]);
-#if CS_X_SWAP
       {
+        // the two half-waves hold the same queries: v_permlane32_swap hands each half the other's
+        // value (no trip through LDS as a cross-lane shuffle would take)
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(t_max), __float_as_uint(t_max), false, false);
         t_max = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
       }
-#else
-      t_max = fmaxf(t_max, __shfl_xor(t_max, 32));
-#endif
       if (__any(t_max > m_run[rb] + slack)) {
         const bool up = t_max > m_run[rb] + slack;
         const float m_new = up ? t_max : m_run[rb];
         const float alpha = up ? __builtin_amdgcn_exp2f((m_run[rb] - m_new) * p.scale_log2e) : 1.f;
-#if CS_X_NORESCALE0
-        const bool fresh = __all(m_run[rb] == kNegInf);
-#else
-        const bool fresh = false;
-#endif
         m_run[rb] = m_new;
         l_run[rb] *= alpha;
-        if (!fresh) {
 #pragma unroll
-          for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[rb][db][r] *= alpha;
-        }
+          for (int r = 0; r < 16; ++r) o[rb][db][r] *= alpha;
       }
       const float m_scaled = (m_run[rb] == kNegInf ? 0.f : m_run[rb]) * p.scale_log2e;
 #pragma unroll
@@ -1074,13 +1195,8 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
           cs::u32x4 w;
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-#if CS_X_NOEXP
-            const float e0 = sacc[rb][kb][8 * mm + 2 * c] - m_scaled;
-            const float e1 = sacc[rb][kb][8 * mm + 2 * c + 1] - m_scaled;
-#else
             const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[rb][kb][8 * mm + 2 * c], p.scale_log2e, -m_scaled));
             const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[rb][kb][8 * mm + 2 * c + 1], p.scale_log2e, -m_scaled));
-#endif
             const uint32_t pk = pack_bf16x2(e0, e1);
             l_run[rb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk),
                                                         __builtin_bit_cast(bf16x2, 0x3f803f80u), l_run[rb], false);
@@ -1090,22 +1206,14 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
         }
     }
     // 16 MFMAs, m = (key block, key half, d block); V^T fragments are read VPF MFMAs ahead
-    constexpr int VPF = CS_X_VPF;
+    constexpr int VPF = 3;
     s16x4 vlo[VPF + 1], vhi[VPF + 1];
-#if CS_X_ADDR
     auto v_frag = [&](int m) {
       const int g0 = (32 * (m >> 3) + 16 * ((m >> 2) & 1)) * D, db = m & 3;
       const uint32_t a = va[db];
       vlo[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(((lds_s16x4*)(static_cast<uintptr_t>(a))) + g0 * 2 / 8);
       vhi[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(((lds_s16x4*)(static_cast<uintptr_t>(a))) + (g0 + 8 * D) * 2 / 8);
     };
-#else
-    auto v_frag = [&](int m) {
-      const int g0 = (32 * (m >> 3) + 16 * ((m >> 2) & 1)) * D, db = m & 3;
-      vlo[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + v_rd[db]]));
-      vhi[m % (VPF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(&tV[g0 + 8 * D + v_rd[db]]));
-    };
-#endif
 #pragma unroll
     for (int m = 0; m < VPF; ++m) v_frag(m);
 #pragma unroll
@@ -1181,13 +1289,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   }
   int stage = 0;
 
-#if CS_X_TS
-  uint32_t ts_vm = 0, ts_bar = 0, ts_book = 0, ts_comp = 0, ts_tail = 0, ts_ncomp = 0, ts_nskip = 0, ts_ep = 0;
-#endif
   for (;;) {
-#if CS_X_TS
-    ts_t ts0 = ts_now();
-#endif
     // everything requested so far has landed: the tile of `cur`, and at an item boundary the Q
     // rows and frontier of its item (telling the compiler so here keeps it from waiting for them
     // later, when that wait would also cover the tile request issued below)
@@ -1199,9 +1301,6 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       asm volatile("" : "+v"(lim_raw[rb]));
     }
     __syncthreads();                     // every wave's share landed; every wave left the other stage
-#if CS_X_TS
-    ts_t ts2 = ts_now();
-#endif
     if (new_item) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) lim[rb] = it_valid[rb] ? lim_raw[rb] : -1;
@@ -1234,20 +1333,9 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       finish_item(ep_tok_head, ep_valid, ep_part);
       ep_pending = false;
     }
-#if CS_X_TS
-    ts_t ts3 = ts_now();
-#endif
     if (computes) compute(cur.kt, stage);
-#if CS_X_TS
-    ts_t ts4 = ts_now();
-#endif
 
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nn.id), "+s"(nn.last_id), "+s"(d3));
-#if CS_X_TS
-    asm volatile("" : "+s"(ts0), "+s"(ts2), "+s"(ts3), "+s"(ts4));
-    TS_ADD(ts_bar, ts0, ts2); TS_ADD(ts_book, ts2, ts3); TS_ADD(ts_comp, ts3, ts4);
-    if (computes) ++ts_ncomp; else ++ts_nskip;
-#endif
     if (cur_last) {
       ep_pending = true;
 #pragma unroll
@@ -1263,21 +1351,12 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
       d0 = d1; d1 = d2; d2 = d3;
       ++seq0;
     }
-#if CS_X_TS
-    { ts_t ts5 = ts_now(); asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(ts5)); TS_ADD(ts_tail, ts4, ts5); }
-#endif
     if (!nxt.live) break;
     cur = nxt;
     nxt = nn;
     stage ^= 1;
   }
   finish_item(ep_tok_head, ep_valid, ep_part);
-#if CS_X_TS
-  if (lane == 0) {
-    uint32_t* t = g_ts + (blockIdx.x * 4 + wave) * 8;
-    t[0] = ts_vm; t[1] = ts_bar; t[2] = ts_book; t[3] = ts_ep; t[4] = ts_comp; t[5] = ts_tail; t[6] = ts_ncomp; t[7] = ts_nskip;
-  }
-#endif
 }
 
 // Merges the partial results of split row tiles: out = sum_c w_c O_c / sum_c w_c l_c with
@@ -1294,7 +1373,7 @@ __global__ __launch_bounds__(256) void window_attn_merge_kernel(AttnParams p) {
   const int rl = (blockIdx.x - item * groups) * 8 + (threadIdx.x >> 5);
   const int row = r_tile + rl;
   if (row >= rows_total) return;
-  const int64_t base = static_cast<int64_t>(item) * p.max_splits * p.bm + rl;
+  const int64_t base = (p.span ? static_cast<int64_t>(d[5]) : static_cast<int64_t>(item) * p.max_splits) * p.bm + rl;
   // one pass, four key ranges at a time: all loads of a batch are independent of each other and
   // of the running maximum (rows a range did not see hold m = -inf, l = 0, O = 0)
   float m_all = kNegInf, l_all = 0.f;
@@ -1413,6 +1492,8 @@ struct AttnPlan {
   int bm;                // rows per item
   int rb;                // 32-row blocks per wave
   int hist_pitch;        // buckets of the planner's counting sort, per XCD
+  int span, pref_pitch;  // span plan (see plan_spans) and the ints per XCD of its prefix array
+  size_t off_pref;
   size_t off_items, off_rt_desc, off_st_toff, off_st_work, off_st_rank, off_rt_stream, off_rt_wgmax,
       off_hist, off_ml, off_o, total;
 };
@@ -1435,13 +1516,12 @@ AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_h
     a.max_splits = (a.max_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
     if (a.max_splits <= 1) { a.max_splits = 1; a.chunk_tiles = 1 << 30; }
   }
-  a.items_cap = a.rt_cap * a.max_splits;
+  a.span = a.max_splits > 1 ? 1 : 0;
+  // span plan: every cut adds one item, and an item's list position names its partial-result slot
+  a.items_cap = a.span ? a.rt_cap + 8 * kSlotsPerXcd : a.rt_cap * a.max_splits;
+  a.pref_pitch = static_cast<int>(a.rt_cap / 8 + 2);
   const int64_t per_xcd = (a.items_cap + 7) / 8;
-#if CS_X_OCC1
-  const int64_t cap = 32;
-#else
   const int64_t cap = a.rb == 2 ? 32 : 64;
-#endif
   a.grid = 8 * static_cast<int>(per_xcd < cap ? per_xcd : cap);
   size_t at = kPlanHeaderInts * sizeof(int32_t);
   auto take = [&](size_t bytes) {
@@ -1459,6 +1539,7 @@ AttnPlan plan_attn(int64_t n_q, int32_t n_streams, int32_t group, int32_t n_kv_h
   const int64_t pair_rounds = (static_cast<int64_t>(n_streams) * n_kv_heads + 7) / 8;
   a.hist_pitch = static_cast<int>((a.max_tiles + 2 > pair_rounds ? a.max_tiles + 2 : pair_rounds) + 1);
   a.off_hist = take(static_cast<size_t>(8) * a.hist_pitch * sizeof(int32_t));
+  a.off_pref = take(static_cast<size_t>(8) * a.pref_pitch * sizeof(int32_t));
   const bool split = a.max_splits > 1;
   a.off_ml = take(split ? static_cast<size_t>(a.items_cap) * a.bm * 2 * sizeof(float) : 0);
   a.off_o = take(split ? static_cast<size_t>(a.items_cap) * a.bm * 128 * sizeof(float) : 0);
@@ -1540,6 +1621,7 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
       p.bm = a.bm;
       p.chunk_tiles = a.chunk_tiles;
       p.max_splits = a.max_splits;
+      p.span = a.span;
       p.ws_plan = reinterpret_cast<const int32_t*>(w);
       p.ws_items = reinterpret_cast<const int32_t*>(w + a.off_items);
       p.ws_desc = reinterpret_cast<int32_t*>(w + a.off_rt_desc);
@@ -1571,6 +1653,9 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         pp.rt_stream = reinterpret_cast<int32_t*>(w + a.off_rt_stream);
         pp.rt_wgmax = reinterpret_cast<int32_t*>(w + a.off_rt_wgmax);
         pp.hist = reinterpret_cast<int32_t*>(w + a.off_hist);
+        pp.span = a.span;
+        pp.pref_pitch = a.pref_pitch;
+        pp.sw_pref = reinterpret_cast<int32_t*>(w + a.off_pref);
         hipLaunchKernelGGL(window_attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, pp);
         const int e = cs::note_hip(hipGetLastError());
         if (e != CS_OK) return e;
@@ -1601,8 +1686,3 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   return cs::note_hip(hipGetLastError());
 }
 
-#if CS_X_TS
-extern "C" int cs_debug_ts(void* host, size_t bytes) {
-  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ts), bytes < sizeof(g_ts) ? bytes : sizeof(g_ts)));
-}
-#endif
