@@ -55,6 +55,9 @@ def parse():
     ap.add_argument("--no-scaled-scoring", action="store_true",
                     help="skip the scaled-batch legs (cs_score_compact, block projection, residual proxy, "
                          "three-axis re-rotation)")
+    ap.add_argument("--no-power-probe", action="store_true",
+                    help="skip the legs that hold a load for a few seconds while sampling power and clock "
+                         "(the matrix-core rate probe and the headline step)")
     ap.add_argument("--side-legs-workload", default="cfg2_qwen7b_32streams",
                     help="the workload whose shapes the side legs (scaled scoring, front end) use when "
                          "several workloads are measured")
@@ -232,6 +235,68 @@ def axes_rerotation(w, step, torch, binding, b_bytes, reps):
                 sections=[n_t, n_h, half - n_t - n_h])
 
 
+def smi_sample():
+    """Socket power (W) and graphics clock (MHz) from `amd-smi metric`, or None where the tool is
+    missing or prints something else.  Reported beside the figures, never used in them."""
+    import re
+    import subprocess
+    try:
+        o = subprocess.run(["amd-smi", "metric", "--power", "--clock"], capture_output=True, text=True, timeout=15).stdout
+        p = re.search(r"SOCKET_POWER:\s*(\d+)", o)
+        c = re.search(r"GFX_0:\s*\n\s*CLK:\s*(\d+)", o)
+        if p and c:
+            return int(p.group(1)), int(c.group(1))
+    except Exception:
+        pass
+    return None
+
+
+def sampled_while(torch, enqueue, seconds):
+    """Keeps the GPU busy with enqueue() for `seconds` and samples power / clock from a thread once
+    the load has been on for a while; returns (samples, calls made, wall seconds)."""
+    import threading
+    samples, stop = [], []
+
+    def sampler():
+        time.sleep(min(1.0, seconds / 3))
+        while not stop:
+            v = smi_sample()
+            if v:
+                samples.append(v)
+            time.sleep(0.3)
+    th = threading.Thread(target=sampler)
+    th.start()
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        enqueue()
+        torch.cuda.synchronize()
+        n += 1
+    wall = time.perf_counter() - t0
+    stop.append(1)
+    th.join()
+    return samples, n, wall
+
+
+def mfma_probe(torch, binding, seconds=1.5):
+    """What the bf16 matrix cores of this device sustain with nothing else running: the library's
+    probe kernel (register operands only) on 2 workgroups per CU, with constant and with
+    pseudo-random operands, each held for `seconds` with power and clock sampled meanwhile."""
+    n_wg, iters = 512, 200000
+    sink = torch.zeros((n_wg * 256,), dtype=torch.float32, device="cuda")
+    flops = n_wg * 4 * iters * 8 * 32768.0
+    out = {}
+    for label, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        binding.cs_mfma_rate_probe(sink, n_wg, 1000, rnd)
+        torch.cuda.synchronize()
+        samples, n, wall = sampled_while(torch, lambda: binding.cs_mfma_rate_probe(sink, n_wg, iters, rnd), seconds)
+        ms = event_time(torch, lambda: binding.cs_mfma_rate_probe(sink, n_wg, iters, rnd), 2)
+        out[label] = dict(TFLOPs=flops / ms / 1e9, frac_of_published_peak=flops / ms / 1e9 / PEAK_MFMA_BF16_TFLOPS,
+                          socket_power_w=max([p for p, _ in samples], default=None),
+                          gfx_clock_mhz=min([c for _, c in samples], default=None))
+    return out
+
+
 def graph_time(torch, run, steps, warmup):
     """Captures run() in a HIP graph (after one eager run on a side stream) and returns the wall
     milliseconds per replay over `steps` replays that follow `warmup` untimed ones."""
@@ -391,7 +456,7 @@ def kernel_rooflines(w, work, t_a, t_plan, t_b, t_c, t_d, traffic_for):
     return out
 
 
-def measure_workload(w, args, torch, binding, engine, keep_for_cpu):
+def measure_workload(w, args, torch, binding, engine, keep_for_cpu, probe_power=False):
     """One workload: the device-planned step in a HIP graph (the figure that counts), the
     host-planned step beside it, event-timed launches of every call, and their rooflines."""
     import numpy as np
@@ -420,6 +485,13 @@ def measure_workload(w, args, torch, binding, engine, keep_for_cpu):
         ms_per_step = 1e3 * (time.perf_counter() - t0) / args.steps
     else:
         ms_per_step, _graph = graph_time(torch, step.run, args.steps, args.warmup)
+    sustained = None
+    if probe_power and not args.eager:
+        # the same graph replayed back to back for a few seconds, power and clock sampled meanwhile
+        samples, n, wall = sampled_while(torch, lambda: [_graph.replay() for _ in range(10)], 3.0)
+        sustained = dict(ms_per_step=1e3 * wall / (10 * n), seconds=wall,
+                         socket_power_w=max([p for p, _ in samples], default=None),
+                         gfx_clock_mhz=min([c for _, c in samples], default=None))
     totals = step.totals.cpu().tolist()
     if totals != [info["n_reuse"], info["n_q"], 0, 0]:
         raise RuntimeError(f"device plan totals {totals} differ from the generator's {info['n_reuse']}, {info['n_q']}")
@@ -466,6 +538,8 @@ def measure_workload(w, args, torch, binding, engine, keep_for_cpu):
                executed_tokens=info["n_q"], reused_rows=info["n_reuse"], window_tokens=info["kv_len_total"],
                reuse_cap=step.reuse_cap, q_cap=step.q_cap, kernels=kernels, roofline=roofline,
                kernel_ms_sum=sum(share.values()))
+    if sustained:
+        res["sustained"] = sustained
     if not args.no_host_plan:
         hstep = engine.DeviceStep(data, host_plan=True)
         if args.eager:
@@ -507,7 +581,8 @@ def main():
     for name in names:
         w = synth.WORKLOADS[name]
         res, data, step, cpu_inputs, work = measure_workload(w, args, torch, binding, engine,
-                                                             keep_for_cpu=(name == headline and not args.no_cpu_baseline))
+                                                             keep_for_cpu=(name == headline and not args.no_cpu_baseline),
+                                                             probe_power=(name == headline and not args.no_power_probe))
         results.append(res)
         reps = max(3, min(args.steps, 20))
         if name == side_name:
@@ -552,6 +627,10 @@ def main():
     }
     if args.calibrate_copy:
         out["copy_calibration"] = copy_calibration(torch)
+    if not args.no_power_probe:
+        out["mfma_probe"] = mfma_probe(torch, binding)
+        if "sustained" in head:
+            out["sustained_headline_step"] = head["sustained"]
     out.update(side)
     if cpu is not None:
         out["cpu_baseline"] = cpu

@@ -67,6 +67,18 @@ const char* cs_version(void);
 int cs_last_hip_error(void);
 
 /* ------------------------------------------------------------------------------------------
+ * Measurement aid (no passage of the paper: it computes nothing of the method).  Launches
+ * n_workgroups workgroups of 256 threads that each issue iters * 8 v_mfma_f32_32x32x16_bf16 per wave
+ * on register operands (constant ones, or lane-dependent pseudo-random ones when random_operands
+ * != 0) and store nothing; 4 waves * iters * 8 * 32768 flop per workgroup.  bench.py times it to
+ * report the bf16 matrix-core rate this device sustains, beside the published peak.
+ *  sink  device float [n_workgroups * 256], never written in practice
+ * Errors: CS_EINVAL (null sink, n_workgroups or iters < 1, n_workgroups > 2^20), CS_EHIP.
+ * ------------------------------------------------------------------------------------------ */
+int cs_mfma_rate_probe(float* sink, int32_t n_workgroups, int32_t iters, int32_t random_operands,
+                       void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * (m) Block-to-patch projection.     Paper Sec. 3.3.1, paragraph on mapping codec changes to ViT
  *     patches: block rectangles live in source-frame pixels, patches in model-input pixels; the
  *     rectangles are rescaled and every patch is given the strongest motion (Eq. 1) found among

@@ -26,7 +26,7 @@ CS_KV_BLOCK = 16
 _ERR = {CS_EINVAL: "CS_EINVAL", CS_EUNSUPPORTED: "CS_EUNSUPPORTED", CS_EHIP: "CS_EHIP",
         CS_EWORKSPACE: "CS_EWORKSPACE"}
 
-EXPORTS = ("cs_version", "cs_last_hip_error", "cs_project_blocks", "cs_residual_proxy", "cs_score_compact_workspace", "cs_score_compact",
+EXPORTS = ("cs_version", "cs_last_hip_error", "cs_mfma_rate_probe", "cs_project_blocks", "cs_residual_proxy", "cs_score_compact_workspace", "cs_score_compact",
            "cs_score_compact_noalloc",
            "cs_plan_refresh_workspace", "cs_plan_refresh", "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
            "cs_window_prefill_attn_workspace",
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
     L.cs_score_compact_noalloc.restype = c.c_int
     L.cs_score_compact_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, u32, u32, i32,
                                            vp, vp, vp, vp]
+    L.cs_mfma_rate_probe.restype = c.c_int
+    L.cs_mfma_rate_probe.argtypes = [vp, i32, i32, i32, vp]
     L.cs_project_blocks.restype = c.c_int
     L.cs_project_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     L.cs_residual_proxy.restype = c.c_int
@@ -125,6 +127,11 @@ def dtype_code(t: torch.Tensor) -> int:
 
 def cs_version() -> str:
     return lib().cs_version().decode()
+
+
+def cs_mfma_rate_probe(sink, n_workgroups, iters, random_operands):
+    _need("cs_mfma_rate_probe", sink, n_workgroups * 256, "sink")
+    _check("cs_mfma_rate_probe", lib().cs_mfma_rate_probe(_ptr(sink), n_workgroups, iters, int(bool(random_operands)), _stream()))
 
 
 def cs_score_compact_workspace(n_streams, n_frames, grid_h, grid_w, group) -> int:

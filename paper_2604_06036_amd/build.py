@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodecsight.so")
-SOURCES = ["library.hip", "project_blocks.hip", "residual_proxy.hip", "score_compact.hip", "plan_refresh.hip", "kv_rerotate.hip", "window_attn.hip"]
+SOURCES = ["library.hip", "calibrate.hip", "project_blocks.hip", "residual_proxy.hip", "score_compact.hip", "plan_refresh.hip", "kv_rerotate.hip", "window_attn.hip"]
 
 # Packed-fp32 VALU forms are switched off for device code (scalar fp32 code generation only).
 HIPCC_FLAGS = [
