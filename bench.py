@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM counters and copy bandwidth)")
+    ap.add_argument("--no-fused-step", action="store_true",
+                    help="skip the leg that times the step with refresh write and attention in one launch")
     ap.add_argument("--no-frontend-step", action="store_true",
                     help="skip the leg that runs the chain from decoder output to attention output")
     ap.add_argument("--no-host-plan", action="store_true",
@@ -540,6 +542,18 @@ def measure_workload(w, args, torch, binding, engine, keep_for_cpu, probe_power=
                kernel_ms_sum=sum(share.values()))
     if sustained:
         res["sustained"] = sustained
+    if not args.no_fused_step and not args.eager:
+        # the same step with each layer's refresh write inside the attention launch (one call per
+        # layer instead of two); reported beside the default route, which stays the one that is faster
+        fstep = engine.DeviceStep(data, reuse_cap=step.reuse_cap, q_cap=step.q_cap, fused=True)
+        res["fused_ms_per_step"], _g3 = graph_time(torch, fstep.run, args.steps, args.warmup)
+        del _g3
+        if fstep.attention_status() != 0:
+            raise RuntimeError("cs_refresh_prefill_attn: the launch-wide wait ran into its bound")
+        t_f = event_time(torch, lambda: [fstep.refresh_and_attention(l, reuse_plan=l > 0) for l in range(L)], reps) / L
+        res["fused_call_ms"] = t_f
+        res["separate_calls_ms"] = t_c + t_d
+        del fstep
     if not args.no_host_plan:
         hstep = engine.DeviceStep(data, host_plan=True)
         if args.eager:

@@ -427,6 +427,47 @@ int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void*
                            int32_t dtype, void* workspace, size_t workspace_bytes,
                            int32_t plan_mode, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * (c+d) Refresh write and joint prefill attention as one call.        Paper Sec. 3.5: at each layer
+ *     the K/V just computed for the refresh and suffix tokens are written straight into the
+ *     destination cache, ahead of that layer's causal attention over the mixed cache, with no
+ *     separate refresh pass.
+ *
+ * Exactly cs_kv_refresh_scatter(k_new, v_new, slot, ..., n_tok, ...) followed by
+ * cs_window_prefill_attn(q, ..., plan_mode, ...) on the same layer, same arguments, same results
+ * bit for bit.  CS_BF16 with head_dim 128: ONE launch: every workgroup of the persistent attention
+ * grid first moves its share of the new rows (stores written through to memory at device scope),
+ * the grid meets at a launch-wide barrier, then attention proceeds as in cs_window_prefill_attn; a
+ * CS_ATTN_PLAN_BUILD call is preceded by the planning launch, a CS_ATTN_PLAN_ONLY call plans and
+ * moves nothing.  Other shapes: the two calls are queued one after the other.
+ *
+ * The barrier needs the whole grid (at most 512 workgroups, two per CU) resident at once, which a
+ * device with all 256 CUs free for the launch gives.  Its wait is bounded so that every wave exits;
+ * if it ever expires (part of the grid could not become resident) the 32-bit word at byte offset
+ * CS_ATTN_STATUS_OFFSET of the workspace is 1 after the call has completed and the call's results
+ * are not valid; it is 0 otherwise (the planning launch clears it).
+ *
+ * Measured on MI355X the one launch takes as long as the two calls for a single stream and 5-10 %
+ * longer for batches of 32-64 streams (there the row move is bandwidth-bound, so the launch saved
+ * is smaller than the barrier added): a caller picks it for the single call site, not for speed.
+ *
+ *  k_new, v_new, slot, n_tok    as in cs_kv_refresh_scatter (slot < 0 skips the row)
+ *  k_cache_layer, v_cache_layer i/o
+ *  all other arguments          as in cs_window_prefill_attn
+ * Errors: those of the two calls.
+ * ------------------------------------------------------------------------------------------ */
+#define CS_ATTN_STATUS_OFFSET 56   /* byte offset of the barrier status word in the attention workspace */
+
+int cs_refresh_prefill_attn(const void* k_new, const void* v_new, const int32_t* slot, int64_t n_tok,
+                            const void* q, void* k_cache_layer, void* v_cache_layer,
+                            const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
+                            const int32_t* block_table, int32_t max_blocks, int32_t block_size,
+                            void* out, int64_t n_q, int32_t n_streams,
+                            int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                            int64_t stride_slot, int64_t stride_head, float softmax_scale,
+                            int32_t dtype, void* workspace, size_t workspace_bytes,
+                            int32_t plan_mode, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

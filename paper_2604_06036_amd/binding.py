@@ -30,7 +30,7 @@ EXPORTS = ("cs_version", "cs_last_hip_error", "cs_mfma_rate_probe", "cs_project_
            "cs_score_compact_noalloc",
            "cs_plan_refresh_workspace", "cs_plan_refresh", "cs_kv_rerotate", "cs_kv_rerotate_axes", "cs_kv_refresh_scatter",
            "cs_window_prefill_attn_workspace",
-           "cs_window_prefill_attn")
+           "cs_window_prefill_attn", "cs_refresh_prefill_attn")
 
 
 class CodecSightError(RuntimeError):
@@ -89,6 +89,9 @@ def lib() -> ctypes.CDLL:
     L.cs_window_prefill_attn.restype = c.c_int
     L.cs_window_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, i64, i32, i32, i32,
                                          i32, i64, i64, f32, i32, vp, sz, i32, vp]
+    L.cs_refresh_prefill_attn.restype = c.c_int
+    L.cs_refresh_prefill_attn.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, i64, i32, i32, i32,
+                                          i32, i64, i64, f32, i32, vp, sz, i32, vp]
     _lib = L
     return L
 
@@ -294,3 +297,36 @@ def cs_window_prefill_attn(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len,
         _ptr(block_table), max_blocks, block_size, _ptr(out), n_q, n_streams, n_q_heads, n_kv_heads,
         head_dim, stride_slot, stride_head, softmax_scale, dtype, _ptr(workspace), workspace_bytes,
         plan_mode, _stream()))
+
+
+CS_ATTN_STATUS_OFFSET = 56
+
+
+def cs_refresh_prefill_attn(k_new, v_new, slot, n_tok, q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len,
+                            block_table, max_blocks, block_size, out, n_q, n_streams, n_q_heads, n_kv_heads,
+                            head_dim, stride_slot, stride_head, softmax_scale, dtype, workspace=None,
+                            workspace_bytes=None, plan_mode=CS_ATTN_PLAN_BUILD):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = "cs_refresh_prefill_attn"
+    _need(fn, k_new, n_tok * n_kv_heads * head_dim, "k_new"); _need(fn, v_new, n_tok * n_kv_heads * head_dim, "v_new")
+    _need(fn, slot, n_tok, "slot")
+    _need(fn, q, n_q * n_q_heads * head_dim, "q"); _need(fn, out, n_q * n_q_heads * head_dim, "out")
+    _need(fn, cu_q, n_streams + 1, "cu_q"); _need(fn, q_pos, n_q, "q_pos"); _need(fn, kv_len, n_streams, "kv_len")
+    _need(fn, block_table, n_streams * max_blocks, "block_table")
+    if workspace is not None and workspace.numel() * workspace.element_size() < workspace_bytes:
+        raise ValueError(f"{fn}: workspace tensor smaller than workspace_bytes")
+    _check(fn, lib().cs_refresh_prefill_attn(
+        _ptr(k_new), _ptr(v_new), _ptr(slot), n_tok, _ptr(q), _ptr(k_cache_layer), _ptr(v_cache_layer), _ptr(cu_q),
+        _ptr(q_pos), _ptr(kv_len), _ptr(block_table), max_blocks, block_size, _ptr(out), n_q, n_streams, n_q_heads,
+        n_kv_heads, head_dim, stride_slot, stride_head, softmax_scale, dtype, _ptr(workspace), workspace_bytes,
+        plan_mode, _stream()))
+
+
+def cs_attn_status(workspace) -> int:
+    """The barrier status word cs_refresh_prefill_attn leaves in the attention workspace (0 = good).
+    The caller synchronises first; this only copies the word back."""
+    if workspace is None or workspace.numel() * workspace.element_size() < CS_ATTN_STATUS_OFFSET + 4:
+        return 0
+    flat = workspace.view(-1).view(torch.uint8)
+    return int(flat[CS_ATTN_STATUS_OFFSET:CS_ATTN_STATUS_OFFSET + 4].view(torch.int32).item())

@@ -58,6 +58,14 @@ struct AttnParams {
   int32_t chunk_tiles, max_splits, bm, span;
   const int32_t* ws_plan;   // plan header (list offsets per XCD, row-tile count, end item, first items)
   const int32_t* ws_items;  // item descriptors, 8 ints each, the 8 XCD lists back to back
+  // refresh write fused into the launch (cs_refresh_prefill_attn): rows to write before attention
+  const void* __restrict__ k_new;
+  const void* __restrict__ v_new;
+  const int32_t* __restrict__ new_slot;
+  int64_t n_new;
+  int32_t row_vecs, head_vecs;   // 16-byte vectors per new row / per head
+  int32_t* ws_sync;      // counters of the fused launch's launch-wide barrier (see launch_barrier)
+  int32_t* ws_status;    // its status word
   int32_t* ws_desc;      // [items][8]: q0, rows_total, r_tile, kvh, n_split
   float* ws_ml;          // [items][max_splits][bm][2]: running max (raw score units), row sum
   float* ws_o;           // [items][max_splits][bm][128]: un-normalised output rows
@@ -395,7 +403,13 @@ typedef __attribute__((ext_vector_type(8))) int32_t i32x8;
 constexpr int kSlotsPerXcd = 64;      // persistent workgroups per XCD: 32 CUs x 2
 constexpr int kHdrEndItem = 16, kHdrHeads = 32;
 constexpr int kHdrEntryInts = 32;
-constexpr int kPlanHeaderInts = kHdrHeads + kHdrEntryInts * 8 * kSlotsPerXcd;
+constexpr int kHdrStatus = 14;        // status word of the fused launch's launch-wide wait
+// Behind the entries, the counters of that wait, 256 bytes apart so that they sit in different
+// memory channels: kSyncGroups group counters, the counter of finished groups, the release word.
+constexpr int kSyncGroups = 16, kSyncPitch = 64;
+constexpr int kHdrSyncBase = (kHdrHeads + kHdrEntryInts * 8 * kSlotsPerXcd + kSyncPitch - 1) / kSyncPitch * kSyncPitch;
+constexpr int kSyncInts = (kSyncGroups + 2) * kSyncPitch;
+constexpr int kPlanHeaderInts = kHdrSyncBase + kSyncInts;
 constexpr int kItemFixedCostHalves = 3;  // per-item overhead in half key tiles, for the planner's balance
 constexpr int kPlanThreads = 1024;
 constexpr int kSortMax = 2048;        // streams sorted by work in LDS; beyond, stream order is kept
@@ -569,6 +583,7 @@ __device__ void plan_spans(const PlanParams& pp, int n_rt, int* s_wave, int (*s_
     pp.header[kHdrEndItem + 6] = -1;
     pp.header[kHdrEndItem + 7] = -1;
   }
+  for (int i = tid; i < kSyncInts; i += kPlanThreads) pp.header[kHdrSyncBase + i] = 0;
   for (int i = n_sw + tid; i < pp.r_cap * n_kv; i += kPlanThreads)
     pp.rt_desc[static_cast<int64_t>(i) * 8 + 4] = 0;
   if (tid >= 512) return;
@@ -767,6 +782,7 @@ __global__ __launch_bounds__(kPlanThreads) void window_attn_plan_kernel(PlanPara
     pp.header[kHdrEndItem + 6] = -1;
     pp.header[kHdrEndItem + 7] = -1;
   }
+  for (int i = tid; i < kSyncInts; i += kPlanThreads) pp.header[kHdrSyncBase + i] = 0;
   __threadfence_block();
   __syncthreads();
 
@@ -899,7 +915,67 @@ __device__ __forceinline__ int32_t sload1(const void* ptr) {
 // the whole register file, every K and V fragment read from LDS feeding two MFMAs) passes the same
 // tests but measured 15-25 % slower as it stands: with one wave per SIMD nothing hides the softmax
 // arithmetic unless the loop is software-pipelined by hand, and half the scores land in AGPRs.
-template <int RB>
+constexpr uint32_t kBarrierSpinLimit = 1u << 24;
+
+// Launch-wide barrier of a grid whose workgroups are all resident (at most 2 per CU on 256 CUs, by
+// construction of the persistent grid).  Arrivals are counted in two levels so that no counter takes
+// more than n/16 + 16 read-modify-writes in a row (they execute at the memory side, one after the
+// other per address): workgroup b adds to group counter b & 15; whoever completes a group resets it
+// and adds to the counter of finished groups; whoever completes that resets it and bumps the release
+// word.  Everybody else polls the release word against the value it read before arriving (it cannot
+// have moved yet: a bump needs every arrival, the reader's included).  Which workgroup runs where
+// plays no part in the counting.  The wait is bounded: after kBarrierSpinLimit polls the workgroup
+// raises the status word and goes on, so every wave exits even if part of the grid never became
+// resident; the results of such a launch are not valid and the status word says so.
+//
+// Visibility across the XCDs' L2s: the rows written before the barrier are stored write-through at
+// agent scope (see store_agent) and every wave waits for its stores' acknowledgements, so no L2
+// write-back is needed on arrival (one per workgroup measured 16 us per launch, one per wave 40 us);
+// after the release one thread per workgroup invalidates the CU's vector cache and the XCD's L2
+// (they are shared by the workgroup's waves), which costs nothing measurable.
+__device__ __forceinline__ void launch_barrier(int32_t* sync, int32_t* status, int n_workgroups) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // s_waitcnt vmcnt(0): the stores are acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int32_t* group = sync + (blockIdx.x % kSyncGroups) * kSyncPitch;
+    int32_t* groups_done = sync + kSyncGroups * kSyncPitch;
+    int32_t* release = sync + (kSyncGroups + 1) * kSyncPitch;
+    const int in_group = (n_workgroups - static_cast<int>(blockIdx.x % kSyncGroups) + kSyncGroups - 1) / kSyncGroups;
+    const int n_groups = n_workgroups < kSyncGroups ? n_workgroups : kSyncGroups;
+    const int r0 = __hip_atomic_load(release, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool last = false;
+    if (__hip_atomic_fetch_add(group, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == in_group - 1) {
+      __hip_atomic_store(group, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (__hip_atomic_fetch_add(groups_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_groups - 1) {
+        __hip_atomic_store(groups_done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(release, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = true;
+      }
+    }
+    if (!last) {
+      uint32_t polls = 0;
+      while (__hip_atomic_load(release, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == r0) {
+        if (++polls > kBarrierSpinLimit) {                // never taken when the whole grid is resident
+          __hip_atomic_store(status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(8);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  }
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// 16-byte store that is written through the XCD's L2 to memory (agent scope), the cache policy an
+// agent-scope atomic store carries: its acknowledgement (vmcnt) comes when the other XCDs can read
+// the bytes, so a wait on vmcnt stands in for an L2 write-back.
+__device__ __forceinline__ void store_agent(void* dst, const cs::u32x4& v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(dst), "v"(v) : "memory");
+}
+
+template <int RB, bool FUSE>
 __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_kernel(AttnParams p) {
   constexpr int WROWS = 32 * RB;        // rows per wave
   constexpr int D = 128;
@@ -914,6 +990,31 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void window_attn_bf16_stream_
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
+
+  if constexpr (FUSE) {
+    // ---- refresh write (Sec. 3.5: the K/V just computed go into the destination cache before
+    //      attention reads it): the whole grid moves the new rows, 16 bytes of K and of V per
+    //      thread and turn, then meets at a launch-wide barrier
+    const int64_t n_units = p.n_new * p.row_vecs;
+    const cs::u32x4* kn = static_cast<const cs::u32x4*>(p.k_new);
+    const cs::u32x4* vn = static_cast<const cs::u32x4*>(p.v_new);
+    uint16_t* kc = const_cast<uint16_t*>(static_cast<const uint16_t*>(p.k));
+    uint16_t* vc = const_cast<uint16_t*>(static_cast<const uint16_t*>(p.v));
+    for (int64_t unit = static_cast<int64_t>(blockIdx.x) * 256 + tid; unit < n_units;
+         unit += static_cast<int64_t>(gridDim.x) * 256) {
+      const int64_t tok = unit / p.row_vecs;
+      const int rem = static_cast<int>(unit - tok * p.row_vecs);
+      const int sl = p.new_slot[tok];
+      if (sl < 0) continue;
+      const int head = rem / p.head_vecs, c = rem - head * p.head_vecs;
+      const int64_t dst = static_cast<int64_t>(sl) * p.stride_slot + head * p.stride_head + c * 8;
+      const cs::u32x4 kv = __builtin_nontemporal_load(kn + unit);
+      const cs::u32x4 vv = __builtin_nontemporal_load(vn + unit);
+      store_agent(kc + dst, kv);
+      store_agent(vc + dst, vv);
+    }
+    launch_barrier(p.ws_sync, p.ws_status, static_cast<int>(gridDim.x));
+  }
 
   // ---- this workgroup's items: a chain through the `next` field of the descriptors, dealt by the
   //      planning kernel; three descriptors of look-ahead are kept loaded
@@ -1559,14 +1660,20 @@ extern "C" size_t cs_window_prefill_attn_workspace(int64_t n_q, int32_t n_stream
   return plan_attn(n_q, n_streams, n_q_heads / n_kv_heads, n_kv_heads, max_blocks).total;
 }
 
-extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void* v_cache_layer,
-                                      const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
-                                      const int32_t* block_table, int32_t max_blocks, int32_t block_size,
-                                      void* out, int64_t n_q, int32_t n_streams, int32_t n_q_heads,
-                                      int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
-                                      int64_t stride_head, float softmax_scale, int32_t dtype,
-                                      void* workspace, size_t workspace_bytes, int32_t plan_mode,
-                                      void* stream) {
+namespace {
+
+// The attention call; with k_new != nullptr the launch first writes the new K/V rows into the cache
+// (bf16 / head_dim 128: inside the same launch; other shapes: the caller has already queued the
+// refresh write as a launch of its own).
+int attn_call(const void* q, const void* k_cache_layer, const void* v_cache_layer,
+              const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
+              const int32_t* block_table, int32_t max_blocks, int32_t block_size,
+              void* out, int64_t n_q, int32_t n_streams, int32_t n_q_heads,
+              int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
+              int64_t stride_head, float softmax_scale, int32_t dtype,
+              void* workspace, size_t workspace_bytes, int32_t plan_mode,
+              const void* k_new, const void* v_new, const int32_t* new_slot, int64_t n_new,
+              void* stream) {
   if (n_q < 0 || n_streams < 0 || n_q_heads < 1 || n_kv_heads < 1 || max_blocks < 0) return CS_EINVAL;
   if (stride_slot < 0 || stride_head < 0) return CS_EINVAL;
   if (n_q_heads % n_kv_heads) return CS_EINVAL;
@@ -1606,6 +1713,15 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   p.scale = softmax_scale;
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   p.n_q = n_q;
+  const bool fuse = k_new != nullptr;
+  p.k_new = k_new;
+  p.v_new = v_new;
+  p.new_slot = new_slot;
+  p.n_new = n_new;
+  p.head_vecs = head_dim / 8;
+  p.row_vecs = n_kv_heads * p.head_vecs;
+  p.ws_sync = nullptr;
+  p.ws_status = nullptr;
   hipStream_t st = cs::as_stream(stream);
   if (dtype == CS_BF16) {
     const size_t bt_bytes = static_cast<size_t>(max_blocks) * sizeof(int32_t);
@@ -1623,6 +1739,8 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
       p.max_splits = a.max_splits;
       p.span = a.span;
       p.ws_plan = reinterpret_cast<const int32_t*>(w);
+      p.ws_sync = reinterpret_cast<int32_t*>(w) + kHdrSyncBase;
+      p.ws_status = reinterpret_cast<int32_t*>(w) + kHdrStatus;
       p.ws_items = reinterpret_cast<const int32_t*>(w + a.off_items);
       p.ws_desc = reinterpret_cast<int32_t*>(w + a.off_rt_desc);
       p.ws_ml = reinterpret_cast<float*>(w + a.off_ml);
@@ -1661,7 +1779,10 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
         if (e != CS_OK) return e;
         if (plan_mode == CS_ATTN_PLAN_ONLY) return CS_OK;
       }
-      hipLaunchKernelGGL(window_attn_bf16_stream_kernel<1>, dim3(static_cast<unsigned>(a.grid)), dim3(256), 0, st, p);
+      if (fuse)
+        hipLaunchKernelGGL((window_attn_bf16_stream_kernel<1, true>), dim3(static_cast<unsigned>(a.grid)), dim3(256), 0, st, p);
+      else
+        hipLaunchKernelGGL((window_attn_bf16_stream_kernel<1, false>), dim3(static_cast<unsigned>(a.grid)), dim3(256), 0, st, p);
       if (a.max_splits > 1) {
         const int e = cs::note_hip(hipGetLastError());
         if (e != CS_OK) return e;
@@ -1686,3 +1807,48 @@ extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, 
   return cs::note_hip(hipGetLastError());
 }
 
+}  // namespace
+
+extern "C" int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void* v_cache_layer,
+                                      const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
+                                      const int32_t* block_table, int32_t max_blocks, int32_t block_size,
+                                      void* out, int64_t n_q, int32_t n_streams, int32_t n_q_heads,
+                                      int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
+                                      int64_t stride_head, float softmax_scale, int32_t dtype,
+                                      void* workspace, size_t workspace_bytes, int32_t plan_mode,
+                                      void* stream) {
+  return attn_call(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks, block_size, out,
+                   n_q, n_streams, n_q_heads, n_kv_heads, head_dim, stride_slot, stride_head, softmax_scale, dtype,
+                   workspace, workspace_bytes, plan_mode, nullptr, nullptr, nullptr, 0, stream);
+}
+
+extern "C" int cs_refresh_prefill_attn(const void* k_new, const void* v_new, const int32_t* slot, int64_t n_tok,
+                                       const void* q, void* k_cache_layer, void* v_cache_layer,
+                                       const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
+                                       const int32_t* block_table, int32_t max_blocks, int32_t block_size,
+                                       void* out, int64_t n_q, int32_t n_streams, int32_t n_q_heads,
+                                       int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
+                                       int64_t stride_head, float softmax_scale, int32_t dtype,
+                                       void* workspace, size_t workspace_bytes, int32_t plan_mode,
+                                       void* stream) {
+  if (n_tok < 0) return CS_EINVAL;
+  const bool one_launch = dtype == CS_BF16 && head_dim == 128;
+  const bool plan_only = plan_mode == CS_ATTN_PLAN_ONLY && one_launch;
+  if (n_tok > 0 && !plan_only && (!k_new || !v_new || !slot)) return CS_EINVAL;
+  if (!cs::aligned16(k_new) || !cs::aligned16(v_new)) return CS_EUNSUPPORTED;
+  if (!one_launch || n_tok == 0 || n_q == 0 || n_streams == 0) {
+    // shapes without a persistent kernel (fp32 caches, head_dim 64), or nothing to attend: the
+    // refresh write as a launch of its own, then the attention call
+    if (n_tok > 0) {
+      const int e = cs_kv_refresh_scatter(k_new, v_new, slot, k_cache_layer, v_cache_layer, n_tok, n_kv_heads,
+                                          head_dim, stride_slot, stride_head, dtype, stream);
+      if (e != CS_OK) return e;
+    }
+    return attn_call(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks, block_size, out,
+                     n_q, n_streams, n_q_heads, n_kv_heads, head_dim, stride_slot, stride_head, softmax_scale, dtype,
+                     workspace, workspace_bytes, plan_mode, nullptr, nullptr, nullptr, 0, stream);
+  }
+  return attn_call(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks, block_size, out,
+                   n_q, n_streams, n_q_heads, n_kv_heads, head_dim, stride_slot, stride_head, softmax_scale, dtype,
+                   workspace, workspace_bytes, plan_mode, k_new, v_new, slot, n_tok, stream);
+}

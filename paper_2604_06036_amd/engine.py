@@ -169,12 +169,13 @@ class DeviceStep:
     (tests and comparison runs)."""
 
     def __init__(self, data: StepData, reuse_cap: Optional[int] = None, q_cap: Optional[int] = None,
-                 host_plan: bool = False):
+                 host_plan: bool = False, fused: bool = False):
         import torch
         from . import binding as cs
         self.cs = cs
         self.data = data
         self.host_plan = host_plan
+        self.fused = fused             # refresh write inside the attention launch (cs_refresh_prefill_attn)
         w = data.workload
         dev = torch.device("cuda")
         self.dev = dev
@@ -293,6 +294,25 @@ class DeviceStep:
                                        self.ws_d if self.ws_d_bytes else None, self.ws_d_bytes,
                                        self.cs.CS_ATTN_PLAN_REUSE if reuse_plan else self.cs.CS_ATTN_PLAN_BUILD)
 
+    def refresh_and_attention(self, layer: int, reuse_plan: bool = False):
+        """Refresh write + attention of one layer as one call (one launch for bf16 / head_dim 128)."""
+        w = self.data.workload
+        self.cs.cs_refresh_prefill_attn(self.k_new[layer], self.v_new[layer], self.q_slot, self.n_q,
+                                        self.q[layer], self.k_pool[layer], self.v_pool[layer], self.cu_q,
+                                        self.q_pos, self.kv_len, self.block_table, self.max_blocks,
+                                        self.cs.CS_KV_BLOCK, self.out[layer], self.n_q, w.n_streams,
+                                        w.n_q_heads, w.n_kv_heads, w.head_dim, self.stride_slot,
+                                        self.stride_head, self.data.softmax_scale, self.dtype,
+                                        self.ws_d if self.ws_d_bytes else None, self.ws_d_bytes,
+                                        self.cs.CS_ATTN_PLAN_REUSE if reuse_plan else self.cs.CS_ATTN_PLAN_BUILD)
+
+    def attention_status(self) -> int:
+        """Barrier status word of the fused launches (synchronises): 0 unless a launch's grid could not
+        become resident as a whole."""
+        import torch
+        torch.cuda.synchronize()
+        return self.cs.cs_attn_status(self.ws_d) if self.ws_d_bytes else 0
+
     def prepare(self):
         """Scoring and planning: everything the layer loop needs in device memory."""
         # scoring updates the accumulated mask in place; a repeated run (graph replay) starts from
@@ -307,8 +327,11 @@ class DeviceStep:
         self.prepare()
         self.rerotate()
         for layer in range(self.data.workload.n_layers):
-            self.refresh_scatter(layer)
-            self.attention(layer, reuse_plan=layer > 0)
+            if self.fused:
+                self.refresh_and_attention(layer, reuse_plan=layer > 0)
+            else:
+                self.refresh_scatter(layer)
+                self.attention(layer, reuse_plan=layer > 0)
 
 
 DevicePlannedStep = DeviceStep     # former name of the device-planned step

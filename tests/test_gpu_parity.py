@@ -865,6 +865,122 @@ def test_attention_plan_modes(cs):
     run(2, ws2, cs.CS_ATTN_PLAN_REUSE)
 
 
+FUSED_CASES = [
+    # dtype, Hq, Hkv, d, kv_lens, n_qs
+    ("bf16", 28, 4, 128, [915], [425]),                        # split sweeps (merge kernel after the fused launch)
+    ("bf16", 32, 8, 128, [300, 1, 640, 77], [100, 1, 333, 0]),
+    ("bf16", 28, 4, 128, [1100 + 13 * i for i in range(32)], [380 + 5 * i for i in range(32)]),   # all 512 workgroups busy
+    ("bf16", 8, 2, 128, [3000, 700, 40], [257, 64, 40]),
+    ("bf16", 4, 4, 64, [200, 129], [64, 129]),                 # head_dim 64: two launches behind the one call
+    ("f32", 2, 1, 64, [452], [332]),                           # fp32: two launches behind the one call
+]
+
+
+@pytest.mark.parametrize("case", range(len(FUSED_CASES)))
+def test_refresh_prefill_attn_equals_scatter_then_attention(cs, case):
+    """The fused call against the oracle's refresh write followed by its attention (the executed
+    tokens' own K/V rows go to the slots of their window positions first, so every query sees fresh
+    rows written by other workgroups of the same launch), and bit for bit against the two separate
+    calls; repeated on the same workspace with the plan reused and other data."""
+    dtype, hq, hkv, d, kv_lens, n_qs = FUSED_CASES[case]
+    say(f"refresh_prefill_attn case {case}: {dtype} heads={hq}/{hkv} d={d} kv={kv_lens} n_q={n_qs}")
+    rng = np.random.default_rng(6100 + case)
+    n_streams = len(kv_lens)
+    nb = [(-(-L // 16)) for L in kv_lens]
+    max_blocks = max(nb) + 1
+    n_blocks = sum(nb) + 3
+    ids = rng.permutation(n_blocks)
+    bt = np.zeros((n_streams, max_blocks), np.int32)
+    at = 0
+    for s in range(n_streams):
+        bt[s, : nb[s]] = ids[at: at + nb[s]]
+        at += nb[s]
+    q_pos, cu = [], [0]
+    for s in range(n_streams):
+        pos = np.sort(rng.choice(kv_lens[s], size=n_qs[s], replace=False)) if n_qs[s] else np.zeros(0, int)
+        q_pos.append(pos)
+        cu.append(cu[-1] + pos.size)
+    q_pos = np.concatenate(q_pos).astype(np.int32)
+    cu = np.asarray(cu, np.int32)
+    n_q = int(q_pos.size)
+    slot = np.concatenate([bt[s, q_pos[cu[s]: cu[s + 1]] // 16].astype(np.int64) * 16 + q_pos[cu[s]: cu[s + 1]] % 16
+                           for s in range(n_streams)]).astype(np.int32)
+    pad = 37                                                     # list padded beyond the executed rows
+    slot_p = np.concatenate([slot, np.full(pad, -1, np.int32)])
+    scale = 1.0 / math.sqrt(d)
+    code = cs.CS_BF16 if dtype == "bf16" else cs.CS_F32
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    wsb = cs.cs_window_prefill_attn_workspace(n_q + pad, n_streams, hq, hkv, d, max_blocks, code)
+    ws = torch.randint(0, 255, (max(64, wsb),), dtype=torch.uint8, device=DEV)
+    dev = lambda a: torch.from_numpy(a).to(DEV)
+    meta = (dev(cu), dev(np.concatenate([q_pos, np.zeros(pad, np.int32)])), torch.tensor(kv_lens, dtype=torch.int32, device=DEV),
+            dev(bt))
+    for rep, mode in enumerate((cs.CS_ATTN_PLAN_BUILD, cs.CS_ATTN_PLAN_REUSE)):
+        kc, vc = _pool(rng, (n_blocks * 16, hkv, d), dtype), _pool(rng, (n_blocks * 16, hkv, d), dtype)
+        kn, vn = _pool(rng, (n_q + pad, hkv, d), dtype), _pool(rng, (n_q + pad, hkv, d), dtype)
+        q = _pool(rng, (n_q + pad, hq, d), dtype)
+        # oracle: refresh write, then attention over the cache it leaves
+        raw = torch.int16 if dtype == "bf16" else torch.int32
+        k_ref, v_ref = kc.clone(), vc.clone()
+        oc.scatter(k_ref.view(raw).numpy(), kn.view(raw).numpy(), slot_p)
+        oc.scatter(v_ref.view(raw).numpy(), vn.view(raw).numpy(), slot_p)
+        ref = oc.window_attn(hp.f64(q[:n_q]), hp.f64(k_ref), hp.f64(v_ref), cu, q_pos, bt, hq, scale)
+        # the two separate calls
+        k2, v2 = kc.to(DEV), vc.to(DEV)
+        out2 = torch.full((n_q + pad, hq, d), 7.0, dtype=tdt, device=DEV)
+        ws2 = torch.zeros_like(ws)
+        cs.cs_kv_refresh_scatter(kn.to(DEV), vn.to(DEV), dev(slot_p), k2, v2, n_q + pad, hkv, d, k2.stride(0), k2.stride(1), code)
+        cs.cs_window_prefill_attn(q.to(DEV), k2, v2, *meta, max_blocks, 16, out2, n_q + pad, n_streams, hq, hkv, d,
+                                  k2.stride(0), k2.stride(1), scale, code, ws2, wsb)
+        # the fused call
+        k1, v1 = kc.to(DEV), vc.to(DEV)
+        out1 = torch.full((n_q + pad, hq, d), 7.0, dtype=tdt, device=DEV)
+        cs.cs_refresh_prefill_attn(kn.to(DEV), vn.to(DEV), dev(slot_p), n_q + pad, q.to(DEV), k1, v1, *meta, max_blocks, 16,
+                                   out1, n_q + pad, n_streams, hq, hkv, d, k1.stride(0), k1.stride(1), scale, code,
+                                   ws, wsb, mode)
+        torch.cuda.synchronize()
+        if dtype == "bf16" and d == 128:
+            assert cs.cs_attn_status(ws) == 0, "the launch-wide barrier ran into its bound"
+        assert torch.equal(k1.cpu().view(raw), k_ref.view(raw)) and torch.equal(v1.cpu().view(raw), v_ref.view(raw))
+        assert torch.equal(out1.view(raw), out2.view(raw)), f"fused and separate calls differ (pass {rep})"
+        assert torch.all(out1[n_q:].float() == 7.0)
+        say(f"  pass {rep}: {hp.check_attention(out1[:n_q].cpu(), ref, dtype)}")
+
+
+def test_fused_step_equals_the_step_of_separate_calls(cs):
+    """The whole device-planned step with the refresh write inside the attention launch: cache and
+    outputs bit-equal to the step that queues the two calls, also when replayed from a HIP graph."""
+    w = synth.small_variant(synth.CFG2, n_streams=3, n_layers=3)
+    say(f"fused step: {w.name} streams={w.n_streams} layers={w.n_layers}")
+    data = engine.assemble_step(w, engine.hip_scorer, device="cpu")
+    n_reuse, n_q = data.info["n_reuse"], data.info["n_q"]
+    plain = engine.DeviceStep(data, reuse_cap=n_reuse + 64, q_cap=n_q + 64)
+    fused = engine.DeviceStep(data, reuse_cap=n_reuse + 64, q_cap=n_q + 64, fused=True)
+    plain.run()
+    fused.run()
+    assert fused.attention_status() == 0
+    for name in ("k_pool", "v_pool", "out"):
+        assert torch.equal(getattr(plain, name).view(torch.int16), getattr(fused, name).view(torch.int16)), name
+    k0, v0 = data.k_pool.to(DEV), data.v_pool.to(DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fused.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fused.run()
+    for rep in range(3):
+        fused.k_pool.copy_(k0); fused.v_pool.copy_(v0); fused.out.zero_()
+        scratch = torch.randn(1 << 20, device=DEV).sum().item()
+        assert math.isfinite(scratch)
+        graph.replay()
+        assert fused.attention_status() == 0
+        for name in ("k_pool", "v_pool", "out"):
+            assert torch.equal(getattr(plain, name).view(torch.int16), getattr(fused, name).view(torch.int16)), (rep, name)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_nothing_pruned_equals_full_causal(cs, dtype):
     """With every token a query the call is plain causal attention (1040-token tiny window)."""
