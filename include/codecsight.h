@@ -447,9 +447,11 @@ int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void*
  * CS_ATTN_STATUS_OFFSET of the workspace is 1 after the call has completed and the call's results
  * are not valid; it is 0 otherwise (the planning launch clears it).
  *
- * Measured on MI355X the one launch takes as long as the two calls for a single stream and 5-10 %
- * longer for batches of 32-64 streams (there the row move is bandwidth-bound, so the launch saved
- * is smaller than the barrier added): a caller picks it for the single call site, not for speed.
+ * Measured on MI355X as eager calls the one launch is 17 % shorter than the two calls for a single
+ * stream (26 against 32 us) and within 3 % of them for batches of 32-64 streams (there the row move
+ * is bandwidth-bound, so the launch saved is about what the barrier adds); replayed from a HIP
+ * graph, where a kernel boundary costs about 2 us, the step built on it is 3-12 % longer than the
+ * step of separate calls.
  *
  *  k_new, v_new, slot, n_tok    as in cs_kv_refresh_scatter (slot < 0 skips the row)
  *  k_cache_layer, v_cache_layer i/o
