@@ -627,7 +627,8 @@ def _attention_plan(cs, cu, q_pos, kv_lens, bt, hq, hkv):
                               cs.CS_ATTN_PLAN_ONLY)
     torch.cuda.synchronize()
     hdr = ws[: PLAN_HDR_INTS * 4].view(torch.int32).cpu().numpy()
-    off = (PLAN_HDR_INTS * 4 + 255) // 256 * 256
+    # behind the entries: the counters of the fused launch's barrier (18 words, 64 ints apart), then the items
+    off = (((PLAN_HDR_INTS + 63) // 64 * 64 + 18 * 64) * 4 + 255) // 256 * 256
     n_items = int(hdr[8])
     items = ws[off: off + n_items * 32].view(torch.int32).cpu().numpy().reshape(n_items, 8)
     return hdr, items
