@@ -542,10 +542,17 @@ def measure_workload(w, args, torch, binding, engine, keep_for_cpu, probe_power=
                kernel_ms_sum=sum(share.values()))
     if sustained:
         res["sustained"] = sustained
+    res["rerotate_schedule"] = (f"second stream beside the layer loop, {step.layers_per_rerotate} layers per call"
+                                if step.overlap else "one call ahead of the layer loop")
+    if step.overlap and not args.eager:
+        # the same step with the position correction as one call ahead of the layer loop
+        sstep = engine.DeviceStep(data, reuse_cap=step.reuse_cap, q_cap=step.q_cap, overlap=False)
+        res["serial_ms_per_step"], _g4 = graph_time(torch, sstep.run, args.steps, args.warmup)
+        del _g4, sstep
     if not args.no_fused_step and not args.eager:
         # the same step with each layer's refresh write inside the attention launch (one call per
         # layer instead of two); reported beside the default route, which stays the one that is faster
-        fstep = engine.DeviceStep(data, reuse_cap=step.reuse_cap, q_cap=step.q_cap, fused=True)
+        fstep = engine.DeviceStep(data, reuse_cap=step.reuse_cap, q_cap=step.q_cap, fused=True, overlap=False)
         res["fused_ms_per_step"], _g3 = graph_time(torch, fstep.run, args.steps, args.warmup)
         del _g3
         if fstep.attention_status() != 0:
@@ -555,7 +562,7 @@ def measure_workload(w, args, torch, binding, engine, keep_for_cpu, probe_power=
         res["separate_calls_ms"] = t_c + t_d
         del fstep
     if not args.no_host_plan:
-        hstep = engine.DeviceStep(data, host_plan=True)
+        hstep = engine.DeviceStep(data, host_plan=True, overlap=step.overlap)
         if args.eager:
             hstep.run(); torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -633,7 +640,8 @@ def main():
                    "stride_frames": head["stride_frames"], "tokens_per_frame": head["tokens_per_frame"],
                    "executed_tokens": head["executed_tokens"], "reused_rows": head["reused_rows"],
                    "window_tokens": head["window_tokens"], "launch": head["launch"],
-                   "plan": "device (cs_plan_refresh inside the step)"},
+                   "plan": "device (cs_plan_refresh inside the step)",
+                   "rerotate_schedule": head["rerotate_schedule"]},
         "window_tokens_per_s": head["window_tokens_per_s"],
         "kernels": head["kernels"],
         "roofline": head["roofline"],

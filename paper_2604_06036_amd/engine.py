@@ -158,6 +158,9 @@ def assemble_step(w: synth.Workload, scorer: Scorer, device="cpu", with_tensors:
     return data
 
 
+OVERLAP_MIN_BYTES = 1 << 30     # bytes the position correction moves per step from which it runs beside the layer loop
+
+
 class DeviceStep:
     """A step resident on the GPU; each method enqueues exactly one C-ABI call.
 
@@ -169,13 +172,19 @@ class DeviceStep:
     (tests and comparison runs)."""
 
     def __init__(self, data: StepData, reuse_cap: Optional[int] = None, q_cap: Optional[int] = None,
-                 host_plan: bool = False, fused: bool = False):
+                 host_plan: bool = False, fused: bool = False, overlap: Optional[bool] = None,
+                 layers_per_rerotate: int = 4):
         import torch
         from . import binding as cs
         self.cs = cs
         self.data = data
         self.host_plan = host_plan
         self.fused = fused             # refresh write inside the attention launch (cs_refresh_prefill_attn)
+        # overlap: the position correction runs on a second stream, a few layers per call, while the
+        # layer loop proceeds; a layer's attention waits for the call that covers its layer
+        # (decided below, once the capacities are known; None = by the size of the correction's traffic)
+        self.overlap = overlap
+        self.layers_per_rerotate = max(1, int(layers_per_rerotate))
         w = data.workload
         dev = torch.device("cuda")
         self.dev = dev
@@ -203,6 +212,14 @@ class DeviceStep:
         self.q_cap = n_q if q_cap is None else int(q_cap)
         if self.q_cap < n_q or self.reuse_cap < n_reuse:
             raise ValueError("capacities below the step's row counts")
+        if self.overlap is None:
+            # measured on MI355X: beside the layer loop the correction gains 1-4 % of the step once it
+            # moves a gigabyte or more (32-64 streams, long dense windows) and loses 1-9 % below that,
+            # where its calls are launch-bound
+            elem = 2 if w.dtype == "bf16" else 4
+            traffic = 4 * self.reuse_cap * w.n_layers * w.n_kv_heads * w.head_dim * elem
+            self.overlap = traffic >= OVERLAP_MIN_BYTES
+        self.side = torch.cuda.Stream() if self.overlap else None      # default priority
         old, new = data.old_layout, data.new_layout
         self.block_table = to(new.block_table)
         self.max_blocks = int(new.block_table.shape[1])
@@ -266,13 +283,16 @@ class DeviceStep:
                                 self.cu_q, self.kv_len, self.new_types_out, self.new_counts_out, self.totals,
                                 self.ws_p, self.ws_p_bytes)
 
-    def rerotate(self, in_place: bool = False):
+    def rerotate(self, in_place: bool = False, layers=None):
+        """Position correction of the reused rows; `layers` = (first, end) restricts the call to a range
+        of layers (the rows of a layer are independent of every other layer's)."""
         w = self.data.workload
         if self.reuse_cap == 0:
             return
-        self.cs.cs_kv_rerotate(self.k_pool, None if in_place else self.v_pool, self.src_slot,
+        l0, l1 = layers if layers is not None else (0, w.n_layers)
+        self.cs.cs_kv_rerotate(self.k_pool[l0:l1], None if in_place else self.v_pool[l0:l1], self.src_slot,
                                None if in_place else self.dst_slot, self.delta,
-                               int(self.src_slot.shape[0]) if self.reuse_cap else 0, w.n_layers, w.n_kv_heads,
+                               int(self.src_slot.shape[0]) if self.reuse_cap else 0, l1 - l0, w.n_kv_heads,
                                w.head_dim, self.stride_layer, self.stride_slot, self.stride_head, w.rope_base,
                                self.cs.CS_ROPE_HALF_SPLIT, self.dtype)
 
@@ -324,14 +344,40 @@ class DeviceStep:
 
     def run(self):
         """One pass of the whole hot path."""
+        import torch
         self.prepare()
-        self.rerotate()
-        for layer in range(self.data.workload.n_layers):
+        n_layers = self.data.workload.n_layers
+        ready = {}
+        if self.overlap and self.reuse_cap:
+            # Sec. 3.5: the position correction needs the plan and the cached rows only, and layer l's
+            # attention needs layer l's corrected rows only.  It is bandwidth work and attention is
+            # matrix-core work, so it runs beside the layer loop on a second stream (fork and join
+            # are stream waits, so a graph capture of this method records them as edges).
+            main = torch.cuda.current_stream()
+            self.side.wait_stream(main)
+            with torch.cuda.stream(self.side):
+                for l0 in range(0, n_layers, self.layers_per_rerotate):
+                    l1 = min(n_layers, l0 + self.layers_per_rerotate)
+                    self.rerotate(layers=(l0, l1))
+                    ev = torch.cuda.Event()
+                    ev.record(self.side)
+                    ready[l0] = ev
+        else:
+            self.rerotate()
+        for layer in range(n_layers):
+            if layer in ready:
+                # the refresh write touches other rows than the correction, but the fused call reads the cache too
+                if self.fused:
+                    torch.cuda.current_stream().wait_event(ready[layer])
             if self.fused:
                 self.refresh_and_attention(layer, reuse_plan=layer > 0)
             else:
                 self.refresh_scatter(layer)
+                if layer in ready:
+                    torch.cuda.current_stream().wait_event(ready[layer])
                 self.attention(layer, reuse_plan=layer > 0)
+        if ready:
+            torch.cuda.current_stream().wait_stream(self.side)
 
 
 DevicePlannedStep = DeviceStep     # former name of the device-planned step

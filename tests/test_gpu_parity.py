@@ -982,6 +982,43 @@ def test_fused_step_equals_the_step_of_separate_calls(cs):
             assert torch.equal(getattr(plain, name).view(torch.int16), getattr(fused, name).view(torch.int16)), (rep, name)
 
 
+@pytest.mark.parametrize("layers_per_call", [1, 2, 5])
+def test_step_with_rerotation_beside_the_layer_loop_equals_the_serial_step(cs, layers_per_call):
+    """The position correction queued on a second stream, a few layers per call, each layer's
+    attention waiting for the call that covers it: cache and outputs bit-equal to the step that
+    corrects all layers first, eagerly and replayed from a HIP graph (the fork and join are edges
+    of the captured graph)."""
+    w = synth.small_variant(synth.CFG2, n_streams=3, n_layers=5)
+    say(f"overlapped step: {w.name} streams={w.n_streams} layers={w.n_layers} layers per call={layers_per_call}")
+    data = engine.assemble_step(w, engine.hip_scorer, device="cpu")
+    n_reuse, n_q = data.info["n_reuse"], data.info["n_q"]
+    serial = engine.DeviceStep(data, reuse_cap=n_reuse + 64, q_cap=n_q + 64, overlap=False)
+    beside = engine.DeviceStep(data, reuse_cap=n_reuse + 64, q_cap=n_q + 64, overlap=True, layers_per_rerotate=layers_per_call)
+    assert not serial.overlap and beside.overlap
+    serial.run()
+    beside.run()
+    torch.cuda.synchronize()
+    for name in ("k_pool", "v_pool", "out"):
+        assert torch.equal(getattr(serial, name).view(torch.int16), getattr(beside, name).view(torch.int16)), name
+    k0, v0 = data.k_pool.to(DEV), data.v_pool.to(DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        beside.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        beside.run()
+    for rep in range(3):
+        beside.k_pool.copy_(k0); beside.v_pool.copy_(v0); beside.out.zero_()
+        assert math.isfinite(torch.randn(1 << 20, device=DEV).sum().item())
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("k_pool", "v_pool", "out"):
+            assert torch.equal(getattr(serial, name).view(torch.int16), getattr(beside, name).view(torch.int16)), (rep, name)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_nothing_pruned_equals_full_causal(cs, dtype):
     """With every token a query the call is plain causal attention (1040-token tiny window)."""
