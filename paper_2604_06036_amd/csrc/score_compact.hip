@@ -32,6 +32,7 @@ constexpr int kSweep = cs::kWave * kGroupsPerSweep;      // token locations per 
 constexpr uint64_t kFlagAggregate = 1ull << 62;
 constexpr uint64_t kFlagPrefix = 1ull << 63;
 constexpr uint32_t kSpinLimit = 1u << 24;
+constexpr int kEmitAhead = 4;                            // sweeps whose keep words the emit launch requests ahead
 constexpr int kMaskWords = 128;                          // ballot words a wave keeps in LDS between the passes
 
 struct ScoreParams {
@@ -478,6 +479,65 @@ __global__ __launch_bounds__(kWavesPerTile * cs::kWave) void score_compact_kerne
   } else {
     base = p.wg_total[tile];                                         // exclusive prefix by now
     for (int w = 0; w < wave; ++w) base += p.wave_total[gw - wave + w];
+  }
+  if constexpr (MODE == kEmitOnly && PK) {
+    // The frames of a wave's streams are one contiguous run of keep bytes.  Taken a sweep at a time
+    // the pass is a chain of dependent round trips (one 4-byte load per lane in flight); here the
+    // keep words of kEmitAhead sweeps are requested before the first of them is ranked.
+    const int spf = (p.n_tok + kSweep - 1) / kSweep;                 // sweeps per frame
+    const int n_sw = (f_stop - f_first) * spf;
+    auto keep_word = [&](int f, int t0) -> uint32_t {
+      const int t = t0 + 4 * lane;
+      return t < p.n_tok ? *reinterpret_cast<const uint32_t*>(p.keep + static_cast<size_t>(f) * p.n_tok + t) : 0u;
+    };
+    int pf = f_first, pt = 0;                                         // next sweep to request
+    int f = f_first, t0 = 0;                                          // next sweep to rank
+    uint32_t ring[kEmitAhead];
+#pragma unroll
+    for (int d = 0; d < kEmitAhead; ++d) {
+      ring[d] = d < n_sw ? keep_word(pf, pt) : 0u;
+      pt += kSweep;
+      if (pt >= p.n_tok) { pt = 0; ++pf; }
+    }
+    for (int q = 0; q < n_sw; q += kEmitAhead) {
+      uint32_t cur[kEmitAhead];
+#pragma unroll
+      for (int d = 0; d < kEmitAhead; ++d) cur[d] = ring[d];
+#pragma unroll
+      for (int d = 0; d < kEmitAhead; ++d) {
+        ring[d] = q + kEmitAhead + d < n_sw ? keep_word(pf, pt) : 0u;
+        pt += kSweep;
+        if (pt >= p.n_tok) { pt = 0; ++pf; }
+      }
+#pragma unroll
+      for (int d = 0; d < kEmitAhead; ++d) {
+        if (q + d < n_sw) {
+          if (t0 == 0 && lane == 0) p.kept_off[f] = static_cast<int32_t>(base);
+          uint64_t mask[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) mask[k] = __ballot(((cur[d] >> (8 * k)) & 0xffu) != 0);
+          uint32_t rank = 0, total = 0;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            rank += lanes_below(mask[k]);
+            total += __popcll(mask[k]);
+          }
+          const int32_t id = f * p.n_tok + t0 + 4 * lane;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if ((mask[k] >> lane) & 1) {
+              p.kept_idx[base + rank] = id + k;
+              ++rank;
+            }
+          }
+          base += total;
+          t0 += kSweep;
+          if (t0 >= p.n_tok) { t0 = 0; ++f; }
+        }
+      }
+    }
+    if (s_end == p.n_streams && n_mine > 0 && lane == 0) p.kept_off[p.n_frames] = static_cast<int32_t>(base);
+    return;
   }
   for (int i = 0; i < n_mine; ++i) {
     const int f0 = __builtin_amdgcn_readlane(cu_l, i), f1 = __builtin_amdgcn_readlane(cu_l, i + 1);
