@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM counters and copy bandwidth)")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="queue the position correction as one call ahead of the layer loop on every workload "
+                         "(the schedule the per-call counters in profiles/ are taken with)")
     ap.add_argument("--no-fused-step", action="store_true",
                     help="skip the leg that times the step with refresh write and attention in one launch")
     ap.add_argument("--no-frontend-step", action="store_true",
@@ -466,7 +469,8 @@ def measure_workload(w, args, torch, binding, engine, keep_for_cpu, probe_power=
     data = engine.assemble_step(w, engine.hip_scorer, device="cuda")
     info = data.info
     cap = lambda n: (n + n // 8 + 255) // 256 * 256
-    step = engine.DevicePlannedStep(data, reuse_cap=cap(info["n_reuse"]), q_cap=cap(info["n_q"]))
+    step = engine.DeviceStep(data, reuse_cap=cap(info["n_reuse"]), q_cap=cap(info["n_q"]),
+                             overlap=False if args.no_overlap else None)
     cpu_inputs = None
     if keep_for_cpu:                       # a sample of the pre-step cache rows for the oracle's re-rotation leg
         rows = int(data.plan.src_slot.shape[0])
