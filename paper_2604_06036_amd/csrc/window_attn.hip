@@ -53,8 +53,9 @@ struct AttnParams {
   int64_t n_q;
   // split-KV (max_splits > 1): a row tile whose key sweep is longer than chunk_tiles key tiles is
   // shared by several work items; their un-normalised partial results go to the workspace and a
-  // second kernel merges them (merging in the last workgroup to finish was tried and is far
-  // slower here: the device-scope release/acquire it needs writes back and invalidates the L2)
+  // second kernel merges them (merging in the last workgroup to finish was built twice and is far
+  // slower here, also with write-through stores in place of an L2 write-back: single stream,
+  // 919 keys, 42 against 23 us per call; 6,033 keys 133 against 117; 17,630 keys 310 against 290)
   int32_t chunk_tiles, max_splits, bm, span;
   const int32_t* ws_plan;   // plan header (list offsets per XCD, row-tile count, end item, first items)
   const int32_t* ws_items;  // item descriptors, 8 ints each, the 8 XCD lists back to back
@@ -915,6 +916,20 @@ __device__ __forceinline__ int32_t sload1(const void* ptr) {
 // the whole register file, every K and V fragment read from LDS feeding two MFMAs) passes the same
 // tests but measured 15-25 % slower as it stands: with one wave per SIMD nothing hides the softmax
 // arithmetic unless the loop is software-pipelined by hand, and half the scores land in AGPRs.
+// 16-byte store that is written through the XCD's L2 to memory (agent scope), the cache policy an
+// agent-scope atomic store carries: its acknowledgement (vmcnt) comes when the other XCDs can read
+// the bytes, so a wait on vmcnt stands in for an L2 write-back.  The s_nop belongs to the store: a
+// store of more than 8 bytes reads its data registers for a cycle after it issues, the compiler
+// does not know that this statement is such a store, and it is free to reuse the data registers in
+// the very next instruction (seen in an experiment: the next row's address landed in the first
+// 8 bytes of a stored row).
+__device__ __forceinline__ void store_agent(void* dst, const cs::u32x4& v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" :: "v"(dst), "v"(v) : "memory");
+}
+// Waits for the acknowledgements of this wave's stores.  Spelled out: the compiler does not know of
+// stores issued from inline assembly, so a fence of its own may come without the wait.
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 constexpr uint32_t kBarrierSpinLimit = 1u << 24;
 
 // Launch-wide barrier of a grid whose workgroups are all resident (at most 2 per CU on 256 CUs, by
@@ -934,7 +949,8 @@ constexpr uint32_t kBarrierSpinLimit = 1u << 24;
 // after the release one thread per workgroup invalidates the CU's vector cache and the XCD's L2
 // (they are shared by the workgroup's waves), which costs nothing measurable.
 __device__ __forceinline__ void launch_barrier(int32_t* sync, int32_t* status, int n_workgroups) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // s_waitcnt vmcnt(0): the stores are acknowledged
+  wait_stores();                                           // the row stores are acknowledged
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (threadIdx.x == 0) {
     int32_t* group = sync + (blockIdx.x % kSyncGroups) * kSyncPitch;
@@ -966,13 +982,6 @@ __device__ __forceinline__ void launch_barrier(int32_t* sync, int32_t* status, i
   }
   __syncthreads();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
-// 16-byte store that is written through the XCD's L2 to memory (agent scope), the cache policy an
-// agent-scope atomic store carries: its acknowledgement (vmcnt) comes when the other XCDs can read
-// the bytes, so a wait on vmcnt stands in for an L2 write-back.
-__device__ __forceinline__ void store_agent(void* dst, const cs::u32x4& v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(dst), "v"(v) : "memory");
 }
 
 template <int RB, bool FUSE>
