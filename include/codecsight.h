@@ -445,7 +445,9 @@ int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void*
  * device with all 256 CUs free for the launch gives.  Its wait is bounded so that every wave exits;
  * if it ever expires (part of the grid could not become resident) the 32-bit word at byte offset
  * CS_ATTN_STATUS_OFFSET of the workspace is 1 after the call has completed and the call's results
- * are not valid; it is 0 otherwise (the planning launch clears it).
+ * are not valid; it is 0 otherwise (the planning launch clears it, together with the barrier's
+ * counters: after a call that raised the word, plan again with CS_ATTN_PLAN_BUILD before the
+ * workspace serves another call).
  *
  * Measured on MI355X as eager calls the one launch is 17 % shorter than the two calls for a single
  * stream (26 against 32 us) and within 3 % of them for batches of 32-64 streams (there the row move
