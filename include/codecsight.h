@@ -458,7 +458,8 @@ int cs_window_prefill_attn(const void* q, const void* k_cache_layer, const void*
  *  k_new, v_new, slot, n_tok    as in cs_kv_refresh_scatter (slot < 0 skips the row)
  *  k_cache_layer, v_cache_layer i/o
  *  all other arguments          as in cs_window_prefill_attn
- * Errors: those of the two calls.
+ * Errors: those of the two calls; the attention call's arguments are checked before anything is
+ * queued, so a call that returns an argument error has moved no row.
  * ------------------------------------------------------------------------------------------ */
 #define CS_ATTN_STATUS_OFFSET 56   /* byte offset of the barrier status word in the attention workspace */
 

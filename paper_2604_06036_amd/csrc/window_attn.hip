@@ -1674,6 +1674,38 @@ namespace {
 // The attention call; with k_new != nullptr the launch first writes the new K/V rows into the cache
 // (bf16 / head_dim 128: inside the same launch; other shapes: the caller has already queued the
 // refresh write as a launch of its own).
+// The argument checks of the attention call that need no device: an error code, CS_OK (go on), or
+// kAttnNothingToDo (valid arguments, empty launch).
+constexpr int kAttnNothingToDo = 1;
+
+int attn_validate(const void* q, const void* k_cache_layer, const void* v_cache_layer,
+                  const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
+                  const int32_t* block_table, int32_t max_blocks, int32_t block_size,
+                  const void* out, int64_t n_q, int32_t n_streams, int32_t n_q_heads,
+                  int32_t n_kv_heads, int32_t head_dim, int64_t stride_slot,
+                  int64_t stride_head, float softmax_scale, int32_t dtype, int32_t plan_mode) {
+  if (n_q < 0 || n_streams < 0 || n_q_heads < 1 || n_kv_heads < 1 || max_blocks < 0) return CS_EINVAL;
+  if (stride_slot < 0 || stride_head < 0) return CS_EINVAL;
+  if (n_q_heads % n_kv_heads) return CS_EINVAL;
+  if (!(softmax_scale > 0.f) || !isfinite(softmax_scale)) return CS_EINVAL;   // also rejects NaN
+  if (dtype != CS_F32 && dtype != CS_BF16) return CS_EUNSUPPORTED;
+  if (head_dim != 64 && head_dim != 128) return CS_EUNSUPPORTED;
+  if (block_size != CS_KV_BLOCK) return CS_EUNSUPPORTED;
+  if (n_q_heads / n_kv_heads > 16) return CS_EUNSUPPORTED;
+  const int elems = dtype == CS_BF16 ? 8 : 4;
+  if (stride_slot % elems || stride_head % elems) return CS_EUNSUPPORTED;
+  if (n_q == 0 || n_streams == 0) return kAttnNothingToDo;
+  const bool plan_only = plan_mode == CS_ATTN_PLAN_ONLY && dtype == CS_BF16 && head_dim == 128;
+  if (!cu_q || !q_pos || !kv_len || !block_table) return CS_EINVAL;
+  if (!plan_only && (!q || !k_cache_layer || !v_cache_layer || !out)) return CS_EINVAL;
+  if (!cs::aligned16(q) || !cs::aligned16(out) || !cs::aligned16(k_cache_layer) ||
+      !cs::aligned16(v_cache_layer))
+    return CS_EUNSUPPORTED;
+  if (n_q * n_q_heads >= (1ll << 31)) return CS_EUNSUPPORTED;
+  if (dtype == CS_BF16 && head_dim == 64 && max_blocks > kMaxBlocksInLds) return CS_EUNSUPPORTED;
+  return CS_OK;
+}
+
 int attn_call(const void* q, const void* k_cache_layer, const void* v_cache_layer,
               const int32_t* cu_q, const int32_t* q_pos, const int32_t* kv_len,
               const int32_t* block_table, int32_t max_blocks, int32_t block_size,
@@ -1683,25 +1715,12 @@ int attn_call(const void* q, const void* k_cache_layer, const void* v_cache_laye
               void* workspace, size_t workspace_bytes, int32_t plan_mode,
               const void* k_new, const void* v_new, const int32_t* new_slot, int64_t n_new,
               void* stream) {
-  if (n_q < 0 || n_streams < 0 || n_q_heads < 1 || n_kv_heads < 1 || max_blocks < 0) return CS_EINVAL;
-  if (stride_slot < 0 || stride_head < 0) return CS_EINVAL;
-  if (n_q_heads % n_kv_heads) return CS_EINVAL;
-  if (!(softmax_scale > 0.f) || !isfinite(softmax_scale)) return CS_EINVAL;   // also rejects NaN
-  if (dtype != CS_F32 && dtype != CS_BF16) return CS_EUNSUPPORTED;
-  if (head_dim != 64 && head_dim != 128) return CS_EUNSUPPORTED;
-  if (block_size != CS_KV_BLOCK) return CS_EUNSUPPORTED;
+  const int checked = attn_validate(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks,
+                                    block_size, out, n_q, n_streams, n_q_heads, n_kv_heads, head_dim, stride_slot,
+                                    stride_head, softmax_scale, dtype, plan_mode);
+  if (checked == kAttnNothingToDo) return CS_OK;
+  if (checked != CS_OK) return checked;
   const int group = n_q_heads / n_kv_heads;
-  if (group > 16) return CS_EUNSUPPORTED;
-  const int elems = dtype == CS_BF16 ? 8 : 4;
-  if (stride_slot % elems || stride_head % elems) return CS_EUNSUPPORTED;
-  if (n_q == 0 || n_streams == 0) return CS_OK;
-  const bool plan_only = plan_mode == CS_ATTN_PLAN_ONLY && dtype == CS_BF16 && head_dim == 128;
-  if (!cu_q || !q_pos || !kv_len || !block_table) return CS_EINVAL;
-  if (!plan_only && (!q || !k_cache_layer || !v_cache_layer || !out)) return CS_EINVAL;
-  if (!cs::aligned16(q) || !cs::aligned16(out) || !cs::aligned16(k_cache_layer) ||
-      !cs::aligned16(v_cache_layer))
-    return CS_EUNSUPPORTED;
-  if (n_q * n_q_heads >= (1ll << 31)) return CS_EUNSUPPORTED;
 
   AttnParams p;
   p.q = q;
@@ -1847,7 +1866,12 @@ extern "C" int cs_refresh_prefill_attn(const void* k_new, const void* v_new, con
   if (!cs::aligned16(k_new) || !cs::aligned16(v_new)) return CS_EUNSUPPORTED;
   if (!one_launch || n_tok == 0 || n_q == 0 || n_streams == 0) {
     // shapes without a persistent kernel (fp32 caches, head_dim 64), or nothing to attend: the
-    // refresh write as a launch of its own, then the attention call
+    // refresh write as a launch of its own, then the attention call (whose arguments are checked
+    // first, so that a call that fails has moved nothing)
+    const int checked = attn_validate(q, k_cache_layer, v_cache_layer, cu_q, q_pos, kv_len, block_table, max_blocks,
+                                      block_size, out, n_q, n_streams, n_q_heads, n_kv_heads, head_dim, stride_slot,
+                                      stride_head, softmax_scale, dtype, plan_mode);
+    if (checked < 0) return checked;
     if (n_tok > 0) {
       const int e = cs_kv_refresh_scatter(k_new, v_new, slot, k_cache_layer, v_cache_layer, n_tok, n_kv_heads,
                                           head_dim, stride_slot, stride_head, dtype, stream);

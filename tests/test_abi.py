@@ -186,6 +186,37 @@ def test_host_side_argument_errors(lib):
     assert attn(ws=one, wsb=need - 1) == binding.CS_EWORKSPACE
     assert attn(ws=one, wsb=need, mode=7) == binding.CS_EINVAL
     assert attn(hkv=4, hq=4, ns=1 << 23, ws=one, wsb=1 << 40) == binding.CS_EUNSUPPORTED
+    assert attn(scale=0.0) == binding.CS_EINVAL
+    assert attn(scale=float("nan")) == binding.CS_EINVAL
+    assert attn(scale=-0.1) == binding.CS_EINVAL
+
+    # (c+d) the fused call: its own checks, then those of the two calls
+    def fused(**kw):
+        a = dict(kn=one, vn=one, slot=one, nt=8, q=one, k=one, v=one, cu=one, pos=one, kvl=one, bt=one, maxb=4, bs=16,
+                 out=one, nq=8, ns=1, hq=4, hkv=2, d=128, ss=256, sh=128, scale=0.1, dt=1, ws=z, wsb=0, mode=0)
+        a.update(kw)
+        return L.cs_refresh_prefill_attn(a["kn"], a["vn"], a["slot"], a["nt"], a["q"], a["k"], a["v"], a["cu"], a["pos"],
+                                         a["kvl"], a["bt"], a["maxb"], a["bs"], a["out"], a["nq"], a["ns"], a["hq"],
+                                         a["hkv"], a["d"], a["ss"], a["sh"], a["scale"], a["dt"], a["ws"], a["wsb"],
+                                         a["mode"], z)
+    assert fused(nt=-1) == binding.CS_EINVAL
+    assert fused(kn=z) == binding.CS_EINVAL
+    assert fused(slot=z) == binding.CS_EINVAL
+    assert fused(kn=ctypes.c_void_p(8)) == binding.CS_EUNSUPPORTED          # not 16-byte aligned
+    assert fused() == binding.CS_EWORKSPACE                                 # bf16 / 128: the plan needs the workspace
+    assert fused(ws=one, wsb=need, mode=7) == binding.CS_EINVAL
+    assert fused(scale=0.0, ws=one, wsb=need) == binding.CS_EINVAL
+    assert fused(d=96) == binding.CS_EUNSUPPORTED
+    assert fused(nq=0, nt=0) == binding.CS_OK
+
+    # the scoring call that allocates nothing serves up to 4,096 streams
+    assert L.cs_score_compact_noalloc(one, z, z, one, one, z, 4097, 1, 16, 16, 1, 0, 0, 0, one, one, one, z) == binding.CS_EUNSUPPORTED
+
+    # the measurement aid
+    assert L.cs_mfma_rate_probe(z, 1, 1, 0, z) == binding.CS_EINVAL
+    assert L.cs_mfma_rate_probe(one, 0, 1, 0, z) == binding.CS_EINVAL
+    assert L.cs_mfma_rate_probe(one, 1, 0, 1, z) == binding.CS_EINVAL
+    assert L.cs_mfma_rate_probe(one, (1 << 20) + 1, 1, 1, z) == binding.CS_EINVAL
 
 
 def test_product_package_does_not_import_the_oracle():
