@@ -212,6 +212,9 @@ class DeviceStep:
         self.q_cap = n_q if q_cap is None else int(q_cap)
         if self.q_cap < n_q or self.reuse_cap < n_reuse:
             raise ValueError("capacities below the step's row counts")
+        if self.overlap is None and self.fused:
+            # the fused launch wants the device to itself: its barrier waits for the whole grid to be resident
+            self.overlap = False
         if self.overlap is None:
             # measured on MI355X: beside the layer loop the correction gains 1-4 % of the step once it
             # moves a gigabyte or more (32-64 streams, long dense windows) and loses 1-9 % below that,
